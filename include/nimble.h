@@ -1,0 +1,188 @@
+/*
+ * nimble.h - C ABI of the dynamic-shape dense / batch_matmul / LSTM-cell path
+ * for AMD Instinct MI355X (gfx950).
+ *
+ * The call order is the one the paper prescribes for an operator whose leading
+ * dimension is Any (Section 3.2, Section 3.3 and the listing of Appendix A):
+ *
+ *   1. the caller reads the run-time shapes of the inputs (host metadata),
+ *   2. the caller runs the operator's shape function (nimble_*_shape, host,
+ *      int64) which yields the output shape and performs the type check that
+ *      could not be done while the dimension was unknown,
+ *   3. the caller allocates the output from that shape (nimble_storage_bytes),
+ *   4. the caller invokes the operator with inputs AND outputs passed
+ *      explicitly (the invoke_mut convention); inside, a dispatch function
+ *      picks one pre-built kernel from the run-time M and its residue
+ *      M mod tile (Section 3.5) and launches it.
+ *
+ * Conventions for every nimble_*_dyn entry point
+ *   - all tensor pointers are DEVICE pointers owned by the caller, row-major,
+ *     contiguous, 16-byte aligned (NIMBLE_ERR_ALIGN otherwise);
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     the call enqueues work and returns, it never synchronises, allocates or
+ *     frees; `workspace` is caller-owned device scratch of `workspace_bytes`
+ *     (query the need with the matching nimble_*_plan; may be NULL when 0);
+ *   - return value: NIMBLE_OK (0) or a negative nimble_status; on any error
+ *     nothing is launched and outputs are untouched; nimble_last_error()
+ *     returns a thread-local description;
+ *   - an extent of 0 for the dynamic dimension (or batch) is a legal
+ *     instantiation of Any: NIMBLE_OK, nothing launched;
+ *   - bf16 = bfloat16 bit patterns (uint16), f32 = IEEE binary32.
+ */
+#ifndef NIMBLE_H_
+#define NIMBLE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nimble_status {
+  NIMBLE_OK = 0,
+  NIMBLE_ERR_NULL = -1,      /* a required pointer is NULL                              */
+  NIMBLE_ERR_RANK = -2,      /* an input has the wrong rank                             */
+  NIMBLE_ERR_SHAPE = -3,     /* run-time type-relation violation (Section 3.1, 3.2)     */
+  NIMBLE_ERR_DTYPE = -4,     /* unknown dtype selector                                  */
+  NIMBLE_ERR_ALIGN = -5,     /* a device pointer is not 16-byte aligned                 */
+  NIMBLE_ERR_WORKSPACE = -6, /* workspace smaller than the plan requires                */
+  NIMBLE_ERR_HIP = -7,       /* the HIP runtime refused the launch                      */
+  NIMBLE_ERR_ARG = -8        /* negative extent, unknown epilogue or variant, overflow  */
+} nimble_status;
+
+/* Epilogue fused into the dense kernel (the shape function of the fused
+ * operator is the dense one: element-wise ops are data independent, Section 3.2). */
+typedef enum nimble_epilogue {
+  NIMBLE_EPI_NONE = 0,          /* y = x.w^T                                     */
+  NIMBLE_EPI_BIAS = 1,          /* y = x.w^T + b                                 */
+  NIMBLE_EPI_BIAS_GELU_ERF = 2  /* y = gelu(x.w^T + b), gelu(v)=v/2 (1+erf(v/sqrt 2)) */
+} nimble_epilogue;
+
+typedef enum nimble_dtype { NIMBLE_BF16 = 0, NIMBLE_F32 = 1 } nimble_dtype;
+
+/* The kernel family the dispatch function chooses from.  Every tiled variant
+ * exists in two copies: one compiled for residue r = 0 (no bounds code at
+ * all) and one for r != 0 (the last tile along M is clamped and masked). */
+typedef enum nimble_variant {
+  NIMBLE_VAR_AUTO = -1,
+  NIMBLE_VAR_GENERIC = 0,    /* any M,N,K; fully bounds checked, scalar FMA       */
+  NIMBLE_VAR_SKINNY16 = 1,   /* M tile 16: weights streamed from HBM once         */
+  NIMBLE_VAR_T32x128 = 2,    /* LDS-tiled MFMA, 32 x 128 macro tile               */
+  NIMBLE_VAR_T64x128 = 3,
+  NIMBLE_VAR_T128x128 = 4,
+  NIMBLE_VAR_T256x128 = 5,
+  NIMBLE_VAR_T256x256 = 6,
+  NIMBLE_VAR_COUNT = 7
+} nimble_variant;
+
+/* What the dispatch function decided for one run-time shape (host only). */
+typedef struct nimble_plan {
+  int32_t variant;        /* nimble_variant                                       */
+  int32_t bm, bn, bk;     /* macro tile of the variant                            */
+  int64_t k;              /* floor(M / bm): number of full tiles along M          */
+  int32_t r;              /* M mod bm: the residue the kernel copy is chosen by   */
+  int32_t residue_copy;   /* 1 when the r != 0 copy (or an N/K edge) is launched  */
+  int32_t split_k;        /* K is cut into this many slices (1 = none)            */
+  uint32_t grid[3];       /* launch grid                                          */
+  uint32_t block;         /* threads per workgroup                                */
+  uint64_t workspace_bytes; /* device scratch the launch needs                    */
+} nimble_plan;
+
+/* ----------------------------------------------------------------------------
+ * Host-only integer functions (no device access, no HIP call).
+ * -------------------------------------------------------------------------- */
+
+/* Shape function of dense, data-independent mode (Section 3.2): x is (M,K),
+ * w is (N,K); writes out_shape[0..1] = (M,N).  NIMBLE_ERR_RANK unless both
+ * ranks are 2, NIMBLE_ERR_ARG on a negative extent, NIMBLE_ERR_SHAPE when the
+ * two K differ.  out_shape is written only on success. */
+int nimble_dense_shape(const int64_t* x_shape, int x_rank, const int64_t* w_shape, int w_rank,
+                       int64_t* out_shape);
+
+/* Shape function of batch_matmul: a is (T,M,K); b is (T,N,K) when trans_b != 0,
+ * else (T,K,N); writes out_shape[0..2] = (T,M,N).  Batch and K must agree
+ * (NIMBLE_ERR_SHAPE).  Two dynamic extents that are the same symbol (the
+ * sequence length of attention) are simply equal numbers here (Section 3.1). */
+int nimble_batch_matmul_shape(const int64_t* a_shape, int a_rank, const int64_t* b_shape,
+                              int b_rank, int trans_b, int64_t* out_shape);
+
+/* Shape function of the fused LSTM cell: x (B,Ix), h (B,H), c (B,H),
+ * w (4H, Ix+H) -> h_out (B,H), c_out (B,H); all ranks 2. */
+int nimble_lstm_shape(const int64_t* x_shape, const int64_t* h_shape, const int64_t* c_shape,
+                      const int64_t* w_shape, int64_t* h_out_shape, int64_t* c_out_shape);
+
+/* Bytes of backing storage of a tensor (Section 3.3: alloc_storage(size,
+ * alignment, device)): product of extents times the element size of `dtype`.
+ * Returns the byte count, or a negative nimble_status. */
+int64_t nimble_storage_bytes(const int64_t* shape, int rank, int dtype);
+
+/* Alignment, in bytes, the paper's alloc_storage examples request (64). */
+int64_t nimble_storage_alignment(void);
+
+/* Residue split of a symbolic extent (Section 3.5): x = tile*k + r,
+ * k = floor(x/tile), 0 <= r < tile. */
+int nimble_residue_split(int64_t x, int64_t tile, int64_t* k, int64_t* r);
+
+/* The dispatch function of dense (Section 3.5), host part: from the run-time
+ * (M,N,K) pick the variant, its residue copy, the split of K and the grid.
+ * `force_variant` = NIMBLE_VAR_AUTO lets the table decide; any other value
+ * requests that variant (NIMBLE_ERR_ARG if it cannot run this shape). */
+int nimble_dense_plan(int64_t M, int64_t N, int64_t K, int epilogue, int out_dtype,
+                      int force_variant, nimble_plan* plan);
+
+/* Same for one batch_matmul (grid z = batch). */
+int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b,
+                             int out_dtype, nimble_plan* plan);
+
+/* Same for the fused LSTM cell. */
+int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan);
+
+/* Name of a variant ("skinny16", "t256x128", ...), NULL if out of range. */
+const char* nimble_variant_name(int variant);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* nimble_last_error(void);
+
+/* ----------------------------------------------------------------------------
+ * Device entry points (Section 3.5 kernels behind the dispatch function).
+ * -------------------------------------------------------------------------- */
+
+/* dense with dynamic M:  y[m,n] = epi( sum_k x[m,k] * w[n,k] + bias[n] ).
+ * x [M,K] bf16, w [N,K] bf16, bias [N] bf16 (may be NULL for NIMBLE_EPI_NONE),
+ * y [M,N] of out_dtype.  Accumulation and epilogue in f32.  The run-time type
+ * check of the shape function is repeated (NIMBLE_ERR_SHAPE is impossible
+ * here since one K is passed; negative extents give NIMBLE_ERR_ARG).
+ * `force_variant` as in nimble_dense_plan. */
+int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
+                     int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* batch_matmul with dynamic M (and N or K when they are the same symbol):
+ *   trans_b != 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,n,k]
+ *   trans_b == 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,k,n]
+ * a, b bf16; c of out_dtype; f32 accumulation. */
+int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch, int64_t M,
+                            int64_t N, int64_t K, int trans_b, float alpha, int out_dtype,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* Row softmax between the two attention batch_matmuls: s [rows, cols] f32 ->
+ * p [rows, cols] bf16, p_j = exp(s_j - max s) / sum_j exp(s_j - max s), f32 math. */
+int nimble_softmax_rows_dyn(const void* s_f32, void* p_bf16, int64_t rows, int64_t cols,
+                            void* stream);
+
+/* Fused LSTM cell with dynamic batch B (gate blocks of w and bias in the order
+ * i, f, g, o, H rows each):
+ *   G = [x | h_prev] . w^T + bias;  c_out = sig(f) c_prev + sig(i) tanh(g);
+ *   h_out = sig(o) tanh(c_out).
+ * x [B,Ix] bf16, h_prev [B,H] bf16, w [4H, Ix+H] bf16, bias [4H] bf16,
+ * c_prev [B,H] f32, c_out [B,H] f32 (may alias c_prev), h_out [B,H] bf16 (must
+ * not alias h_prev).  Ix and H must be multiples of 8. */
+int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, const void* bias,
+                          const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t Ix,
+                          int64_t H, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIMBLE_H_ */

@@ -1,0 +1,217 @@
+"""ctypes binding: argument marshalling only, same names as the C ABI."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libnimble_hip.so")
+_HEADER = os.path.join(os.path.dirname(_PKG), "include", "nimble.h")
+
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU_ERF = 0, 1, 2
+BF16, F32 = 0, 1
+VAR_AUTO = -1
+
+_STATUS = {0: "OK", -1: "ERR_NULL", -2: "ERR_RANK", -3: "ERR_SHAPE", -4: "ERR_DTYPE", -5: "ERR_ALIGN",
+           -6: "ERR_WORKSPACE", -7: "ERR_HIP", -8: "ERR_ARG"}
+
+
+class NimbleError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"NIMBLE_{_STATUS.get(code, code)}: {message}")
+        self.code = code
+
+
+class _CPlan(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("bm", ctypes.c_int32), ("bn", ctypes.c_int32),
+                ("bk", ctypes.c_int32), ("k", ctypes.c_int64), ("r", ctypes.c_int32),
+                ("residue_copy", ctypes.c_int32), ("split_k", ctypes.c_int32),
+                ("grid", ctypes.c_uint32 * 3), ("block", ctypes.c_uint32),
+                ("workspace_bytes", ctypes.c_uint64)]
+
+
+@dataclass
+class Plan:
+    variant: int
+    name: str
+    bm: int
+    bn: int
+    bk: int
+    k: int
+    r: int
+    residue_copy: int
+    split_k: int
+    grid: Tuple[int, int, int]
+    block: int
+    workspace_bytes: int
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load the HIP library.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc --offload-arch=gfx950) first")
+    # torch ships its own HIP runtime (same SONAME as the system one).  Import it
+    # first so that this library binds to the runtime that owns torch's streams
+    # and allocations instead of bringing a second runtime into the process.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    ip = ctypes.POINTER(ctypes.c_int64)
+    lib.nimble_dense_shape.argtypes = [ip, i32, ip, i32, ip]
+    lib.nimble_batch_matmul_shape.argtypes = [ip, i32, ip, i32, i32, ip]
+    lib.nimble_lstm_shape.argtypes = [ip, ip, ip, ip, ip, ip]
+    lib.nimble_storage_bytes.argtypes = [ip, i32, i32]
+    lib.nimble_storage_bytes.restype = i64
+    lib.nimble_storage_alignment.restype = i64
+    lib.nimble_residue_split.argtypes = [i64, i64, ip, ip]
+    lib.nimble_dense_plan.argtypes = [i64, i64, i64, i32, i32, i32, ctypes.POINTER(_CPlan)]
+    lib.nimble_batch_matmul_plan.argtypes = [i64, i64, i64, i64, i32, i32, ctypes.POINTER(_CPlan)]
+    lib.nimble_lstm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(_CPlan)]
+    lib.nimble_variant_name.argtypes = [i32]
+    lib.nimble_variant_name.restype = ctypes.c_char_p
+    lib.nimble_last_error.restype = ctypes.c_char_p
+    lib.nimble_dense_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.nimble_batch_matmul_dyn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_float, i32, vp,
+                                            ctypes.c_size_t, vp]
+    lib.nimble_softmax_rows_dyn.argtypes = [vp, vp, i64, i64, vp]
+    lib.nimble_lstm_gates_dyn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+def exported_symbols() -> Sequence[str]:
+    """Names of the functions ``include/nimble.h`` declares."""
+    text = open(_HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nimble_[a-z0-9_]+)\s*\(", text)))
+
+
+def last_error() -> str:
+    return load().nimble_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise NimbleError(rc, last_error())
+
+
+def _arr(shape: Sequence[int]):
+    return (ctypes.c_int64 * max(len(shape), 1))(*[int(s) for s in shape])
+
+
+# ------------------------------------------------------------------ host side
+def nimble_dense_shape(x_shape: Sequence[int], w_shape: Sequence[int]) -> Tuple[int, int]:
+    out = (ctypes.c_int64 * 2)(-1, -1)
+    _check(load().nimble_dense_shape(_arr(x_shape), len(x_shape), _arr(w_shape), len(w_shape), out))
+    return int(out[0]), int(out[1])
+
+
+dense_shape = nimble_dense_shape
+
+
+def batch_matmul_shape(a_shape, b_shape, trans_b: bool) -> Tuple[int, int, int]:
+    out = (ctypes.c_int64 * 3)(-1, -1, -1)
+    _check(load().nimble_batch_matmul_shape(_arr(a_shape), len(a_shape), _arr(b_shape), len(b_shape),
+                                            int(bool(trans_b)), out))
+    return int(out[0]), int(out[1]), int(out[2])
+
+
+def lstm_shape(x_shape, h_shape, c_shape, w_shape):
+    for s in (x_shape, h_shape, c_shape, w_shape):
+        if len(s) != 2:
+            raise NimbleError(-2, "lstm expects rank-2 shapes")
+    ho, co = (ctypes.c_int64 * 2)(-1, -1), (ctypes.c_int64 * 2)(-1, -1)
+    _check(load().nimble_lstm_shape(_arr(x_shape), _arr(h_shape), _arr(c_shape), _arr(w_shape), ho, co))
+    return (int(ho[0]), int(ho[1])), (int(co[0]), int(co[1]))
+
+
+def storage_bytes(shape: Sequence[int], dtype: int) -> int:
+    n = int(load().nimble_storage_bytes(_arr(shape), len(shape), dtype))
+    if n < 0:
+        raise NimbleError(n, last_error())
+    return n
+
+
+def storage_alignment() -> int:
+    return int(load().nimble_storage_alignment())
+
+
+def residue_split(x: int, tile: int) -> Tuple[int, int]:
+    k, r = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().nimble_residue_split(x, tile, ctypes.byref(k), ctypes.byref(r)))
+    return int(k.value), int(r.value)
+
+
+def variant_name(v: int) -> Optional[str]:
+    s = load().nimble_variant_name(v)
+    return s.decode() if s else None
+
+
+def _plan(c: _CPlan) -> Plan:
+    return Plan(c.variant, variant_name(c.variant) or "?", c.bm, c.bn, c.bk, c.k, c.r, c.residue_copy,
+                c.split_k, (c.grid[0], c.grid[1], c.grid[2]), c.block, c.workspace_bytes)
+
+
+def dense_plan(M: int, N: int, K: int, epilogue: int = EPI_BIAS, out_dtype: int = BF16,
+               force_variant: int = VAR_AUTO) -> Plan:
+    c = _CPlan()
+    _check(load().nimble_dense_plan(M, N, K, epilogue, out_dtype, force_variant, ctypes.byref(c)))
+    return _plan(c)
+
+
+def batch_matmul_plan(batch: int, M: int, N: int, K: int, trans_b: bool, out_dtype: int = BF16) -> Plan:
+    c = _CPlan()
+    _check(load().nimble_batch_matmul_plan(batch, M, N, K, int(bool(trans_b)), out_dtype, ctypes.byref(c)))
+    return _plan(c)
+
+
+def lstm_plan(B: int, Ix: int, H: int) -> Plan:
+    c = _CPlan()
+    _check(load().nimble_lstm_plan(B, Ix, H, ctypes.byref(c)))
+    return _plan(c)
+
+
+# ---------------------------------------------------------------- device side
+# Pointers are integers (tensor.data_ptr()); `stream` is a hipStream_t handle as
+# an integer (torch.cuda.current_stream().cuda_stream), 0 for the default one.
+def nimble_dense_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,
+                     out_dtype: int = BF16, force_variant: int = VAR_AUTO, workspace: int = 0,
+                     workspace_bytes: int = 0, stream: int = 0) -> None:
+    _check(load().nimble_dense_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, force_variant, workspace,
+                                   workspace_bytes, stream))
+
+
+def nimble_batch_matmul_dyn(a: int, b: int, c: int, batch: int, M: int, N: int, K: int, trans_b: bool,
+                            alpha: float = 1.0, out_dtype: int = BF16, workspace: int = 0,
+                            workspace_bytes: int = 0, stream: int = 0) -> None:
+    _check(load().nimble_batch_matmul_dyn(a, b, c, batch, M, N, K, int(bool(trans_b)), alpha, out_dtype,
+                                          workspace, workspace_bytes, stream))
+
+
+def nimble_softmax_rows_dyn(s_f32: int, p_bf16: int, rows: int, cols: int, stream: int = 0) -> None:
+    _check(load().nimble_softmax_rows_dyn(s_f32, p_bf16, rows, cols, stream))
+
+
+def nimble_lstm_gates_dyn(x: int, h_prev: int, w: int, bias: int, c_prev: int, c_out: int, h_out: int,
+                          B: int, Ix: int, H: int, workspace: int = 0, workspace_bytes: int = 0,
+                          stream: int = 0) -> None:
+    _check(load().nimble_lstm_gates_dyn(x, h_prev, w, bias, c_prev, c_out, h_out, B, Ix, H, workspace,
+                                        workspace_bytes, stream))

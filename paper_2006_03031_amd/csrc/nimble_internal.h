@@ -1,0 +1,44 @@
+// Internal declarations shared by the host dispatcher and the kernel launchers.
+#ifndef NIMBLE_INTERNAL_H_
+#define NIMBLE_INTERNAL_H_
+
+#include "nimble.h"
+
+namespace nimble {
+
+struct VariantInfo {
+  const char* name;
+  int bm, bn, bk, threads;
+};
+extern const VariantInfo kVariants[NIMBLE_VAR_COUNT];
+
+// Record a message for nimble_last_error() and return `code`.
+int fail(int code, const char* fmt, ...);
+void clear_error();
+
+bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
+
+// Dispatch table shared by dense (batch = 1) and batch_matmul.
+int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int force_variant, nimble_plan* p);
+
+// One C = epi(alpha * A.B^T + bias) problem as the kernels see it.  A is
+// [M,K] with row stride lda, B is [N,K] with row stride ldb (or, when
+// b_is_kn, [K,N] with row stride ldb), C is [M,N] with row stride ldc; strides
+// in elements; batch strides sa/sb/sc in elements.
+struct GemmArgs {
+  const void* a;
+  const void* b;
+  const void* bias;
+  void* c;
+  int M, N, K;
+  int lda, ldb, ldc;
+  long long sa, sb, sc;
+  float alpha;
+  int epilogue;
+  int out_f32;
+  int b_is_kn;
+  int batch;
+};
+
+}  // namespace nimble
+#endif

@@ -1,0 +1,663 @@
+// gfx950 kernels behind the dispatch function (Section 3.5) and the device
+// entry points of the C ABI.  bf16 operands, f32 accumulation on the matrix
+// cores (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_16x16x32_bf16), f32 epilogue.
+//
+// Kernel family
+//   gemm_tile_kernel<BM,BN,WGM,WGN,EDGE>  LDS-staged, double-buffered K tiles of 64.
+//       EDGE=false is the residue-0 copy: no bounds code at all.
+//       EDGE=true  is the residue copy: rows are clamped on load and masked on
+//       store in the last tile along M (and along N / K when those are ragged).
+//   skinny_kernel<MT,LSTM>   M <= 64 per workgroup: the weights are streamed from
+//       HBM exactly once straight into MFMA operands, the four waves of a
+//       workgroup split K and reduce through LDS.  LSTM=true gathers the four
+//       gate rows of four hidden units and applies the cell update in the
+//       epilogue.
+//   generic_kernel            any shape and stride, one thread per output.
+//   softmax_rows_kernel       f32 scores -> bf16 probabilities, one wave per row.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "nimble_internal.h"
+
+namespace nimble {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf2f(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// float32 -> bfloat16, round to nearest, ties to even.
+__device__ __forceinline__ u16 f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+__device__ __forceinline__ float gelu_erf(float v) {
+  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+}
+
+__device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+__device__ __forceinline__ float epilogue(float acc, float alpha, float bias, int epi) {
+  float v = alpha * acc;
+  if (epi != NIMBLE_EPI_NONE) v += bias;
+  if (epi == NIMBLE_EPI_BIAS_GELU_ERF) v = gelu_erf(v);
+  return v;
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// ---------------------------------------------------------------------------
+// Workgroup id -> macro tile.  Workgroups are handed to the 8 XCDs round robin;
+// give each XCD a contiguous run of tile ids so that the tiles sharing rows of
+// A and B meet in that XCD's L2, and walk the tiles in groups of `group_m`
+// tile rows so that the set in flight is a compact block.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
+                                              int group_m, int& tm, int& tn) {
+  const int q = nblocks >> 3, rem = nblocks & 7;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int pid = xcd * q + (xcd < rem ? xcd : rem) + local;
+  const int in_group = group_m * tiles_n;
+  const int gid = pid / in_group;
+  const int first_m = gid * group_m;
+  const int gsize = (tiles_m - first_m) < group_m ? (tiles_m - first_m) : group_m;
+  const int rest = pid - gid * in_group;
+  tm = first_m + rest % gsize;
+  tn = rest / gsize;
+}
+
+// ---------------------------------------------------------------------------
+// LDS-tiled MFMA kernel.
+//   LDS tile layout: row-major rows of 64 bf16 (8 chunks of 16 bytes); chunk c
+//   of row r is stored at chunk slot c ^ (r & 7), which makes both the
+//   row-wise 16-byte writes and the column-of-rows 16-byte fragment reads
+//   conflict free.
+//   MFMA operand roles: the A operand (32 rows i) is a slab of B = weights
+//   (output features n), the B operand (32 columns j) is a slab of A =
+//   activations (rows m).  A lane then owns four consecutive n of one row m in
+//   every group of four accumulator registers, which gives packed stores.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, bool EDGE>
+__global__ void __launch_bounds__(WGM* WGN * 64)
+    gemm_tile_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_LD = BM * 8 / NT, B_LD = BN * 8 / NT;
+  static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the workgroup");
+  static_assert(TM >= 1 && TN >= 1, "wave tile too small");
+  constexpr int ROWS_PER_PASS = NT / 8;
+
+  __shared__ __attribute__((aligned(16))) uint4 As[2][BM * 8];
+  __shared__ __attribute__((aligned(16))) uint4 Bs[2][BN * 8];
+
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int z = blockIdx.z;
+  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa;
+  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb;
+  const int M = g.M, N = g.N, K = g.K;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // global -> LDS assignment: thread handles chunk (tid & 7) of rows (tid >> 3) + i * ROWS_PER_PASS
+  const int ld_row = tid >> 3, ld_c = tid & 7;
+  const int ld_slot = ld_row * 8 + (ld_c ^ (ld_row & 7));  // ROWS_PER_PASS is a multiple of 8
+  const u16* a_src[A_LD];
+  const u16* b_src[B_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    int row = m0 + ld_row + i * ROWS_PER_PASS;
+    if (EDGE) row = row < M ? row : M - 1;
+    a_src[i] = A + (long long)row * g.lda + ld_c * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_LD; ++i) {
+    int row = n0 + ld_row + i * ROWS_PER_PASS;
+    if (EDGE) row = row < N ? row : N - 1;
+    b_src[i] = B + (long long)row * g.ldb + ld_c * 8;
+  }
+
+  // fragment read offsets (in 16-byte chunks)
+  const int fr_row = lane & 31;
+  const int fr_a = (wm * WM + fr_row) * 8;
+  const int fr_b = (wn * WN + fr_row) * 8;
+  const int fr_half = lane >> 5;
+  const int fr_x = lane & 7;
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  uint4 ra[A_LD], rb[B_LD];
+  const int KT = (K + 63) >> 6;
+
+  auto load_global = [&](int kt) {
+    const int k0 = kt << 6;
+    const bool kvalid = !EDGE || (k0 + ld_c * 8 < K);
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i)
+      ra[i] = kvalid ? *(const uint4*)(a_src[i] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i)
+      rb[i] = kvalid ? *(const uint4*)(b_src[i] + k0) : make_uint4(0, 0, 0, 0);
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) As[buf][ld_slot + i * ROWS_PER_PASS * 8] = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) Bs[buf][ld_slot + i * ROWS_PER_PASS * 8] = rb[i];
+  };
+
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_global(kt + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int phys = (kk * 2 + fr_half) ^ fr_x;
+      bf16x8 xa[TM], wb[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) xa[j] = as_bf16x8(As[buf][fr_a + j * 32 * 8 + phys]);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) wb[i] = as_bf16x8(Bs[buf][fr_b + i * 32 * 8 + phys]);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane owns row m, and for accumulator group q the columns
+  // n_base + q*8 + (lane>>5)*4 + 0..3
+  const float alpha = g.alpha;
+  const int epi = g.epilogue;
+  const u16* __restrict__ bias = (const u16*)g.bias;
+  const bool vec_ok = !EDGE || ((g.ldc & 3) == 0);
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm * WM + j * 32 + fr_row;
+    if (EDGE && m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WN + i * 32 + q * 8 + fr_half * 4;
+        if (EDGE && n >= N) continue;
+        float v[4];
+        const bool full4 = !EDGE || (n + 3 < N);
+        if (full4) {
+          float b4[4] = {0.f, 0.f, 0.f, 0.f};
+          if (epi != NIMBLE_EPI_NONE) {
+            const uint2 bb = *(const uint2*)(bias + n);
+            b4[0] = bf2f((u16)(bb.x & 0xffff));
+            b4[1] = bf2f((u16)(bb.x >> 16));
+            b4[2] = bf2f((u16)(bb.y & 0xffff));
+            b4[3] = bf2f((u16)(bb.y >> 16));
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = epilogue(acc[i][j][q * 4 + e], alpha, b4[e], epi);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float be = (epi != NIMBLE_EPI_NONE && n + e < N) ? bf2f(bias[n + e]) : 0.f;
+            v[e] = epilogue(acc[i][j][q * 4 + e], alpha, be, epi);
+          }
+        }
+        const long long off = (long long)z * g.sc + (long long)m * g.ldc + n;
+        if (g.out_f32) {
+          float* C = (float*)g.c + off;
+          if (full4 && vec_ok) {
+            *(float4*)C = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) C[e] = v[e];
+          }
+        } else {
+          u16* C = (u16*)g.c + off;
+          if (full4 && vec_ok) {
+            uint2 pk;
+            pk.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+            pk.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+            *(uint2*)C = pk;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) C[e] = f2bf(v[e]);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Skinny kernel: at most 64 rows of activations per workgroup, 16 weight rows.
+// Every weight element is read from HBM once, by exactly one lane, straight
+// into an MFMA operand (no LDS staging: there is no reuse to stage for).
+// ---------------------------------------------------------------------------
+struct SkinnyArgs {
+  const u16* x;     // [M, K]  (LSTM: [B, Ix])
+  const u16* h;     // LSTM only: [B, H]
+  const u16* w;     // [N, K]  (LSTM: [4H, Ix+H])
+  const u16* bias;  // [N]
+  void* y;          // [M, N] bf16 or f32 (LSTM: h_out [B,H] bf16)
+  const float* c_prev;  // LSTM only
+  float* c_out;         // LSTM only
+  int M, N, K;      // LSTM: M = B, N = 4H, K = Ix + H
+  int Ix, H;        // LSTM only
+  int epilogue, out_f32;
+};
+
+template <int MT, bool LSTM>
+__global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
+  __shared__ float red[4][MT][16][17];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, gq = lane >> 4;
+  const int M = s.M, N = s.N, K = s.K;
+  const int mbase = blockIdx.y * 64;
+
+  // weight row of this lane
+  long long wrow;
+  if (LSTM) {
+    int unit = blockIdx.x * 4 + (r & 3);
+    unit = unit < s.H ? unit : s.H - 1;
+    wrow = (long long)(r >> 2) * s.H + unit;
+  } else {
+    int n = blockIdx.x * 16 + r;
+    wrow = n < N ? n : N - 1;
+  }
+  const u16* __restrict__ wp = s.w + wrow * K + gq * 8;
+
+  // activation rows of this lane, one per 16-row tile
+  const u16* xp[MT];
+  const u16* hp[MT];
+  bool mvalid[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = mbase + t * 16 + r;
+    mvalid[t] = m < M;
+    const int mc = mvalid[t] ? m : 0;
+    if (LSTM) {
+      xp[t] = s.x + (long long)mc * s.Ix;
+      hp[t] = s.h + (long long)mc * s.H - s.Ix;  // indexed with the k of the concatenation
+    } else {
+      xp[t] = s.x + (long long)mc * K;
+      hp[t] = nullptr;
+    }
+  }
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // this wave's contiguous range of 32-wide k steps
+  const int steps = (K + 31) >> 5;
+  const int per_wave = (steps + 3) >> 2;
+  const int s_begin = wave * per_wave;
+  const int s_end = (s_begin + per_wave) < steps ? (s_begin + per_wave) : steps;
+
+  constexpr int U = 8;
+  for (int s0 = s_begin; s0 < s_end; s0 += U) {
+    uint4 wv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = (s0 + u) * 32 + gq * 8;
+      const bool ok = (s0 + u < s_end) && (k < K);
+      wv[u] = ok ? *(const uint4*)(wp + (long long)(s0 + u) * 32) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      uint4 xv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = (s0 + u) * 32 + gq * 8;
+        const bool ok = mvalid[t] && (s0 + u < s_end) && (k < K);
+        const u16* src = (LSTM && k >= s.Ix) ? hp[t] : xp[t];
+        xv[u] = ok ? *(const uint4*)(src + k) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wv[u]), as_bf16x8(xv[u]), acc[t],
+                                                         0, 0, 0);
+    }
+  }
+
+  // accumulator of lane (r, gq), register v: weight row i = 4 gq + v, activation row j = r
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][t][r][gq * 4 + v] = acc[t][v];
+  __syncthreads();
+
+  if (LSTM) {
+    // thread -> (tile t, row m, hidden unit u); the four gates sit at columns gate*4 + u
+    const int t = tid >> 6;
+    if (t < MT) {
+      const int mm = (tid & 63) >> 2, u = tid & 3;
+      const int m = mbase + t * 16 + mm;
+      const int unit = blockIdx.x * 4 + u;
+      if (m < M && unit < s.H) {
+        float gate[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = q * 4 + u;
+          const float sum = (red[0][t][mm][col] + red[1][t][mm][col]) +
+                            (red[2][t][mm][col] + red[3][t][mm][col]);
+          gate[q] = sum + bf2f(s.bias[q * s.H + unit]);
+        }
+        const long long o = (long long)m * s.H + unit;
+        const float cn = sigmoidf(gate[1]) * s.c_prev[o] + sigmoidf(gate[0]) * tanhf(gate[2]);
+        s.c_out[o] = cn;
+        ((u16*)s.y)[o] = f2bf(sigmoidf(gate[3]) * tanhf(cn));
+      }
+    }
+  } else {
+    const int mm = tid >> 4, nn = tid & 15;
+    const int n = blockIdx.x * 16 + nn;
+    if (n < N) {
+      const float b = (s.epilogue != NIMBLE_EPI_NONE) ? bf2f(s.bias[n]) : 0.f;
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        const int m = mbase + t * 16 + mm;
+        if (m < M) {
+          const float sum = (red[0][t][mm][nn] + red[1][t][mm][nn]) +
+                            (red[2][t][mm][nn] + red[3][t][mm][nn]);
+          const float v = epilogue(sum, 1.0f, b, s.epilogue);
+          const long long o = (long long)m * N + n;
+          if (s.out_f32)
+            ((float*)s.y)[o] = v;
+          else
+            ((u16*)s.y)[o] = f2bf(v);
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Fully bounds-checked kernel for any shape, stride and B layout.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) generic_kernel(GemmArgs g) {
+  const int n = blockIdx.x * 16 + (threadIdx.x & 15);
+  const int m = blockIdx.y * 16 + (threadIdx.x >> 4);
+  const int z = blockIdx.z;
+  if (m >= g.M || n >= g.N) return;
+  const u16* __restrict__ a = (const u16*)g.a + (long long)z * g.sa + (long long)m * g.lda;
+  const u16* __restrict__ b = (const u16*)g.b + (long long)z * g.sb;
+  float acc = 0.f;
+  if (g.b_is_kn) {
+    for (int k = 0; k < g.K; ++k) acc = fmaf(bf2f(a[k]), bf2f(b[(long long)k * g.ldb + n]), acc);
+  } else {
+    b += (long long)n * g.ldb;
+    for (int k = 0; k < g.K; ++k) acc = fmaf(bf2f(a[k]), bf2f(b[k]), acc);
+  }
+  const float bias = (g.epilogue != NIMBLE_EPI_NONE) ? bf2f(((const u16*)g.bias)[n]) : 0.f;
+  const float v = epilogue(acc, g.alpha, bias, g.epilogue);
+  const long long o = (long long)z * g.sc + (long long)m * g.ldc + n;
+  if (g.out_f32)
+    ((float*)g.c)[o] = v;
+  else
+    ((u16*)g.c)[o] = f2bf(v);
+}
+
+// ---------------------------------------------------------------------------
+// Row softmax, f32 in, bf16 out; one wave per row, four rows per workgroup.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__global__ void __launch_bounds__(256)
+    softmax_rows_kernel(const float* __restrict__ s, u16* __restrict__ p, long long rows, int cols) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const float* sr = s + row * cols;
+  u16* pr = p + row * cols;
+  float mx = -INFINITY;
+  for (int j = lane; j < cols; j += 64) mx = fmaxf(mx, sr[j]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int j = lane; j < cols; j += 64) sum += expf(sr[j] - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  for (int j = lane; j < cols; j += 64) pr[j] = f2bf(expf(sr[j] - mx) * inv);
+}
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+static int check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return NIMBLE_OK;
+  return fail(NIMBLE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static int launch_tile(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  int group_m = BM >= 128 ? 4 : 8;
+  if (group_m > tiles_m) group_m = tiles_m;
+  dim3 grid(p.grid[0], 1, p.grid[2]), block(WGM * WGN * 64);
+  if (p.residue_copy)
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
+  else
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
+  return check_hip(hipGetLastError(), "tile kernel launch");
+}
+
+template <bool LSTM>
+static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t st) {
+  dim3 grid(p.grid[0], p.grid[1], 1), block(256);
+  const int rows = s.M < 64 ? s.M : 64;
+  const int mt = (rows + 15) / 16;
+  switch (mt) {
+    case 1: hipLaunchKernelGGL((skinny_kernel<1, LSTM>), grid, block, 0, st, s); break;
+    case 2: hipLaunchKernelGGL((skinny_kernel<2, LSTM>), grid, block, 0, st, s); break;
+    case 3: hipLaunchKernelGGL((skinny_kernel<3, LSTM>), grid, block, 0, st, s); break;
+    default: hipLaunchKernelGGL((skinny_kernel<4, LSTM>), grid, block, 0, st, s); break;
+  }
+  return check_hip(hipGetLastError(), "skinny kernel launch");
+}
+
+static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
+  switch (p.variant) {
+    case NIMBLE_VAR_GENERIC: {
+      dim3 grid(p.grid[0], p.grid[1], p.grid[2]), block(256);
+      hipLaunchKernelGGL(generic_kernel, grid, block, 0, st, g);
+      return check_hip(hipGetLastError(), "generic kernel launch");
+    }
+    case NIMBLE_VAR_SKINNY16: {
+      SkinnyArgs s{};
+      s.x = (const u16*)g.a;
+      s.w = (const u16*)g.b;
+      s.bias = (const u16*)g.bias;
+      s.y = g.c;
+      s.M = g.M;
+      s.N = g.N;
+      s.K = g.K;
+      s.epilogue = g.epilogue;
+      s.out_f32 = g.out_f32;
+      return launch_skinny<false>(s, p, st);
+    }
+    case NIMBLE_VAR_T32x128: return launch_tile<32, 128, 1, 4>(g, p, st);
+    case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T128x128: return launch_tile<128, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T256x128: return launch_tile<256, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T256x256: return launch_tile<256, 256, 2, 2>(g, p, st);
+    default: return fail(NIMBLE_ERR_ARG, "unknown variant %d", p.variant);
+  }
+}
+
+static inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace nimble
+
+using namespace nimble;
+
+extern "C" {
+
+int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
+                     int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  (void)workspace;
+  if (M < 0 || N < 0 || K < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
+    return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
+  if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32)
+    return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  nimble_plan p;
+  int rc = plan_dense(1, M, N, K, force_variant, &p);
+  if (rc != NIMBLE_OK) return rc;
+  if (M == 0 || N == 0) return NIMBLE_OK;
+  if (!x || !w || !y) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (epilogue != NIMBLE_EPI_NONE && !bias) return fail(NIMBLE_ERR_NULL, "epilogue needs a bias");
+  if (misaligned(x) || misaligned(w) || misaligned(y) || (bias && misaligned(bias)))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (workspace_bytes < p.workspace_bytes)
+    return fail(NIMBLE_ERR_WORKSPACE, "workspace of %zu bytes, plan needs %llu", workspace_bytes,
+                (unsigned long long)p.workspace_bytes);
+  GemmArgs g{};
+  g.a = x;
+  g.b = w;
+  g.bias = bias;
+  g.c = y;
+  g.M = (int)M;
+  g.N = (int)N;
+  g.K = (int)K;
+  g.lda = (int)K;
+  g.ldb = (int)K;
+  g.ldc = (int)N;
+  g.alpha = 1.0f;
+  g.epilogue = epilogue;
+  g.out_f32 = out_dtype == NIMBLE_F32;
+  g.batch = 1;
+  return launch_gemm(g, p, (hipStream_t)stream);
+}
+
+int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch, int64_t M,
+                            int64_t N, int64_t K, int trans_b, float alpha, int out_dtype,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  (void)workspace;
+  if (batch < 0 || M < 0 || N < 0 || K < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32)
+    return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  nimble_plan p;
+  int rc = nimble_batch_matmul_plan(batch, M, N, K, trans_b, out_dtype, &p);
+  if (rc != NIMBLE_OK) return rc;
+  if (batch == 0 || M == 0 || N == 0) return NIMBLE_OK;
+  if (!a || !b || !c) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (misaligned(a) || misaligned(b) || misaligned(c))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (workspace_bytes < p.workspace_bytes)
+    return fail(NIMBLE_ERR_WORKSPACE, "workspace of %zu bytes, plan needs %llu", workspace_bytes,
+                (unsigned long long)p.workspace_bytes);
+  GemmArgs g{};
+  g.a = a;
+  g.b = b;
+  g.c = c;
+  g.M = (int)M;
+  g.N = (int)N;
+  g.K = (int)K;
+  g.lda = (int)K;
+  g.ldb = trans_b ? (int)K : (int)N;
+  g.ldc = (int)N;
+  g.sa = (long long)M * K;
+  g.sb = (long long)N * K;
+  g.sc = (long long)M * N;
+  g.alpha = alpha;
+  g.epilogue = NIMBLE_EPI_NONE;
+  g.out_f32 = out_dtype == NIMBLE_F32;
+  g.b_is_kn = trans_b ? 0 : 1;
+  g.batch = (int)batch;
+  // batch slices of a K-contiguous operand stay 16-byte aligned only if M*K (N*K) is a multiple of 8
+  if (p.variant != NIMBLE_VAR_GENERIC && (((M * K) & 7) != 0 || ((N * K) & 7) != 0)) {
+    rc = plan_dense(batch, M, N, K, NIMBLE_VAR_GENERIC, &p);
+    if (rc != NIMBLE_OK) return rc;
+  }
+  return launch_gemm(g, p, (hipStream_t)stream);
+}
+
+int nimble_softmax_rows_dyn(const void* s_f32, void* p_bf16, int64_t rows, int64_t cols,
+                            void* stream) {
+  clear_error();
+  if (rows < 0 || cols < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  if (cols > (1ll << 30) || rows > (1ll << 32)) return fail(NIMBLE_ERR_ARG, "extent too large");
+  if (rows == 0 || cols == 0) return NIMBLE_OK;
+  if (!s_f32 || !p_bf16) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (misaligned(s_f32) || misaligned(p_bf16))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  hipLaunchKernelGGL(softmax_rows_kernel, grid, block, 0, (hipStream_t)stream, (const float*)s_f32,
+                     (u16*)p_bf16, (long long)rows, (int)cols);
+  return check_hip(hipGetLastError(), "softmax kernel launch");
+}
+
+int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, const void* bias,
+                          const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t Ix,
+                          int64_t H, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  (void)workspace;
+  (void)workspace_bytes;
+  nimble_plan p;
+  int rc = nimble_lstm_plan(B, Ix, H, &p);
+  if (rc != NIMBLE_OK) return rc;
+  if (B == 0) return NIMBLE_OK;
+  if (!h_prev || !w || !bias || !c_prev || !c_out || !h_out || (Ix > 0 && !x))
+    return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if ((x && misaligned(x)) || misaligned(h_prev) || misaligned(w) || misaligned(bias) ||
+      misaligned(c_prev) || misaligned(c_out) || misaligned(h_out))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (h_out == h_prev) return fail(NIMBLE_ERR_ARG, "h_out must not alias h_prev");
+  SkinnyArgs s{};
+  s.x = (const u16*)x;
+  s.h = (const u16*)h_prev;
+  s.w = (const u16*)w;
+  s.bias = (const u16*)bias;
+  s.y = h_out;
+  s.c_prev = (const float*)c_prev;
+  s.c_out = (float*)c_out;
+  s.M = (int)B;
+  s.N = (int)(4 * H);
+  s.K = (int)(Ix + H);
+  s.Ix = (int)Ix;
+  s.H = (int)H;
+  s.epilogue = NIMBLE_EPI_BIAS;
+  return launch_skinny<true>(s, p, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+"""Caller-side sequence for one dynamic operator, on torch tensors.
+
+For every operator this is the order the paper gives for a tensor whose
+leading dimension is unknown until run time (Section 3.2, Section 3.3,
+Appendix A): read the run-time shapes (host metadata, no device sync), run the
+shape function, allocate the output from the shape it returns, then invoke the
+kernel with inputs and outputs passed explicitly.  torch supplies device memory
+and the stream; all arithmetic runs in the HIP library.
+"""
+from __future__ import annotations
+
+from typing import Optional, Tuple
+
+import torch
+
+from . import binding as nb
+
+_TORCH_DTYPE = {nb.BF16: torch.bfloat16, nb.F32: torch.float32}
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _alloc(shape, dtype: int, device) -> torch.Tensor:
+    # alloc_storage(size, alignment, device) + alloc_tensor(storage, 0, shape, dtype):
+    # torch's caching allocator returns storage aligned to at least 512 bytes.
+    nb.storage_bytes(shape, dtype)  # validates the size computation
+    return torch.empty(tuple(shape), dtype=_TORCH_DTYPE[dtype], device=device)
+
+
+def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilogue: int = nb.EPI_BIAS,
+          out_dtype: int = nb.BF16, force_variant: int = nb.VAR_AUTO,
+          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, N = nb.nimble_dense_shape(tuple(x.shape), tuple(w.shape))
+    K = x.shape[1]
+    y = out if out is not None else _alloc((M, N), out_dtype, x.device)
+    nb.nimble_dense_dyn(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else 0,
+                        y.data_ptr(), M, N, K, epilogue, out_dtype, force_variant, 0, 0, _stream())
+    return y
+
+
+def batch_matmul(a: torch.Tensor, b: torch.Tensor, trans_b: bool, alpha: float = 1.0,
+                 out_dtype: int = nb.BF16, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T, M, N = nb.batch_matmul_shape(tuple(a.shape), tuple(b.shape), trans_b)
+    K = a.shape[2]
+    c = out if out is not None else _alloc((T, M, N), out_dtype, a.device)
+    nb.nimble_batch_matmul_dyn(a.data_ptr(), b.data_ptr(), c.data_ptr(), T, M, N, K, trans_b, alpha,
+                               out_dtype, 0, 0, _stream())
+    return c
+
+
+def softmax_rows(s: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    cols = s.shape[-1]
+    rows = s.numel() // cols if cols else 0
+    p = out if out is not None else _alloc(tuple(s.shape), nb.BF16, s.device)
+    nb.nimble_softmax_rows_dyn(s.data_ptr(), p.data_ptr(), rows, cols, _stream())
+    return p
+
+
+def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+              alpha: float = 0.125) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """S = alpha Q.K^T (f32), P = softmax rows (bf16), O = P.V (bf16)."""
+    s = batch_matmul(q, k, True, alpha, nb.F32)
+    p = softmax_rows(s)
+    o = batch_matmul(p, v, False, 1.0, nb.BF16)
+    return s, p, o
+
+
+def lstm_step(x: torch.Tensor, h: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, c: torch.Tensor,
+              h_out: Optional[torch.Tensor] = None,
+              c_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    (B, H), _ = nb.lstm_shape(tuple(x.shape), tuple(h.shape), tuple(c.shape), tuple(w.shape))
+    Ix = x.shape[1]
+    if h_out is None:
+        h_out = _alloc((B, H), nb.BF16, x.device)
+    if c_out is None:
+        c_out = _alloc((B, H), nb.F32, x.device)
+    nb.nimble_lstm_gates_dyn(x.data_ptr(), h.data_ptr(), w.data_ptr(), bias.data_ptr(), c.data_ptr(),
+                             c_out.data_ptr(), h_out.data_ptr(), B, Ix, H, 0, 0, _stream())
+    return h_out, c_out

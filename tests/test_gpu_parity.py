@@ -1,0 +1,354 @@
+"""Parity of the HIP path with the CPU oracle, element by element, on the same
+seeded bf16-rounded inputs.  Bar: max normwise relative error 5e-3 per call
+(||gpu - ref||_F / ||ref||_F over the call's whole output); shape outputs
+bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+EPI = {"none": 0, "bias": 1, "bias_gelu": 2}
+TILED = {2: (32, 128), 3: (64, 128), 4: (128, 128), 5: (256, 128), 6: (256, 256)}
+
+
+@pytest.fixture(scope="module")
+def rt():
+    import paper_2006_03031_amd as nb
+    from paper_2006_03031_amd import runtime
+    nb.load()  # fails loudly if the HIP library is not built
+    return runtime
+
+
+@pytest.fixture(scope="module")
+def nb():
+    import paper_2006_03031_amd as nb
+    return nb
+
+
+def _dev():
+    from gpu_util import bits_from_dev, f32_to_dev, from_dev, to_dev
+    return to_dev, f32_to_dev, from_dev, bits_from_dev
+
+
+def _err(got, ref):
+    return oracle.normwise_rel_error(got, ref)
+
+
+# ------------------------------------------------------------------ config 1
+def test_config1_all_64_calls(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    calls = wl.config1_calls()
+    w, b = to_dev(calls[0].w), to_dev(calls[0].b)
+    worst = 0.0
+    for c in calls:
+        x = to_dev(c.x)
+        y = rt.dense(x, w, b, nb.EPI_BIAS)
+        assert tuple(y.shape) == oracle.dense_shape(c.x.shape, c.w.shape)
+        ref = oracle.dense(c.x.f32, c.w.f32, c.b.f32, "bias")
+        worst = max(worst, _err(from_dev(y), ref))
+    assert worst <= TOL, worst
+
+
+# ------------------------------------------------------------------ residue sweeps
+def _sweep(rt, nb, variant, N, K, Ms, epilogue="bias_gelu", out_dtype=0, seed=0):
+    """One oracle evaluation at max(Ms) rows serves every M by row-prefix invariance.
+    The output buffer carries a guard band that must stay untouched."""
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng([99, seed, N, K])
+    Mmax = max(Ms)
+    x = wl.uniform_bf16(rng, (Mmax, K))
+    w = wl.normal_bf16(rng, (N, K), std=0.05)
+    b = wl.uniform_bf16(rng, (N,))
+    ref = oracle.dense(x.f32, w.f32, b.f32, epilogue)
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    tdt = torch.bfloat16 if out_dtype == 0 else torch.float32
+    guard = 3
+    worst = 0.0
+    for M in Ms:
+        buf = torch.full((M + guard, N), 768.0, dtype=tdt, device="cuda")
+        rt.dense(xd[:M], wd, bd, EPI[epilogue], out_dtype, variant, out=buf[:M])
+        got = from_dev(buf)
+        assert np.all(got[M:] == 768.0), f"variant {variant} wrote past row M={M}"
+        e = _err(got[:M], ref[:M])
+        assert e <= TOL, (variant, M, N, K, e)
+        worst = max(worst, e)
+    return worst
+
+
+@pytest.mark.parametrize("variant", sorted(TILED))
+def test_tiled_variants_every_residue(rt, nb, variant):
+    bm, bn = TILED[variant]
+    # every M from 1 to 2*tile+1: r takes every value, k = 0, 1, 2
+    _sweep(rt, nb, variant, N=bn * 2, K=128, Ms=range(1, 2 * bm + 2))
+
+
+@pytest.mark.parametrize("variant", sorted(TILED))
+def test_tiled_variants_ragged_N_and_K(rt, nb, variant):
+    bm, bn = TILED[variant]
+    Ms = [1, bm - 1, bm, bm + 1, 2 * bm + 1]
+    _sweep(rt, nb, variant, N=bn + 72, K=200, Ms=Ms, epilogue="bias")          # N % 4 == 0, K % 64 != 0
+    _sweep(rt, nb, variant, N=bn + 37, K=72, Ms=Ms, epilogue="bias_gelu")      # N odd: element-wise tail
+    _sweep(rt, nb, variant, N=24, K=8, Ms=Ms, epilogue="none", out_dtype=1)    # one partial tile, f32 out
+    _sweep(rt, nb, variant, N=bn + 6, K=1024, Ms=Ms, epilogue="bias", out_dtype=1)
+
+
+def test_skinny_every_M_and_ragged_shapes(rt, nb):
+    _sweep(rt, nb, 1, N=2048, K=1024, Ms=range(1, 65))
+    _sweep(rt, nb, 1, N=128, K=128, Ms=range(1, 131), epilogue="bias")      # M > 64: several row blocks
+    _sweep(rt, nb, 1, N=100, K=200, Ms=[1, 15, 16, 17, 33, 64], epilogue="bias")  # N % 16 != 0, K % 32 != 0
+    _sweep(rt, nb, 1, N=37, K=8, Ms=[1, 5, 48], epilogue="none", out_dtype=1)
+    _sweep(rt, nb, 1, N=768, K=3072, Ms=[1, 2, 3, 4, 8, 16, 31, 64], epilogue="bias_gelu")
+
+
+def test_generic_kernel_any_shape(rt, nb):
+    _sweep(rt, nb, 0, N=33, K=7, Ms=[1, 2, 17, 40], epilogue="bias_gelu")
+    _sweep(rt, nb, 0, N=5, K=100, Ms=[3, 16], epilogue="none", out_dtype=1)
+    _sweep(rt, nb, -1, N=130, K=100, Ms=[1, 70, 300], epilogue="bias")  # auto with K % 8 != 0 -> generic
+
+
+def test_auto_dispatch_power_of_two_grid_and_128(rt, nb):
+    # the paper's tuning grid (powers of two up to 256) and its evaluation point M = 128
+    for (K, N, epi) in [(768, 2304, "bias"), (768, 3072, "bias_gelu"), (3072, 768, "bias")]:
+        _sweep(rt, nb, -1, N=N, K=K, Ms=[1, 2, 4, 8, 16, 32, 64, 128, 256], epilogue=epi)
+
+
+def test_identity_and_zero_weights_on_gpu(rt, nb):
+    to_dev, _, from_dev, bits_from_dev = _dev()
+    rng = np.random.default_rng(5)
+    for M, variant in [(7, -1), (100, -1), (300, 4), (300, 6)]:
+        x = wl.uniform_bf16(rng, (M, 256))
+        eye = wl.BF16Array(wl.f32_to_bf16_bits(np.eye(256, dtype=np.float32)), np.eye(256, dtype=np.float32))
+        y = rt.dense(to_dev(x), to_dev(eye), None, nb.EPI_NONE, nb.BF16, variant)
+        assert np.array_equal(bits_from_dev(y), x.bits)  # bit-exact
+        b = wl.uniform_bf16(rng, (256,))
+        zero = wl.BF16Array(np.zeros((256, 256), np.uint16), np.zeros((256, 256), np.float32))
+        y = rt.dense(to_dev(x), to_dev(zero), to_dev(b), nb.EPI_BIAS, nb.BF16, variant)
+        assert np.array_equal(bits_from_dev(y), np.broadcast_to(b.bits, (M, 256)))
+        y = rt.dense(to_dev(x), to_dev(zero), to_dev(b), nb.EPI_NONE, nb.F32, variant)
+        assert np.all(from_dev(y) == 0)
+
+
+def test_row_prefix_invariance_on_gpu(rt, nb):
+    # with one kernel variant, rows do not depend on how large M was
+    to_dev, _, _, bits_from_dev = _dev()
+    rng = np.random.default_rng(6)
+    x, w, b = wl.uniform_bf16(rng, (513, 256)), wl.normal_bf16(rng, (256, 256)), wl.uniform_bf16(rng, (256,))
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    for variant in (4, 5, 6):
+        full = bits_from_dev(rt.dense(xd, wd, bd, nb.EPI_BIAS_GELU_ERF, nb.BF16, variant))
+        for M in (1, 255, 256, 257, 400):
+            part = bits_from_dev(rt.dense(xd[:M], wd, bd, nb.EPI_BIAS_GELU_ERF, nb.BF16, variant))
+            assert np.array_equal(part, full[:M])
+
+
+# ------------------------------------------------------------------ config 3
+def test_config3_bert_base_gemms(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    Ls = sorted(set([1, 512] + [int(v) for v in wl.config3_lengths()[:6]]))
+    weights = [wl.dense_weights(3, i, N, K) for i, (_, K, N, _) in enumerate(wl.BERT_BASE_GEMMS)]
+    dweights = [(to_dev(w), to_dev(b)) for w, b in weights]
+    for d, L in enumerate(Ls):
+        for i, (name, K, N, epi) in enumerate(wl.BERT_BASE_GEMMS):
+            x = wl.activations(3, d * 10 + i, L, K)
+            y = rt.dense(to_dev(x), dweights[i][0], dweights[i][1], EPI[epi])
+            assert tuple(y.shape) == (L, N)
+            ref = oracle.dense(x.f32, weights[i][0].f32, weights[i][1].f32, epi)
+            e = _err(from_dev(y), ref)
+            assert e <= TOL, (name, L, e)
+
+
+# ------------------------------------------------------------------ config 5
+def _sampled_rows(M, bm_max, n_random, rng):
+    tail = np.arange(max(0, M - 2 * bm_max), M)
+    head = rng.choice(max(1, M - len(tail)), size=min(n_random, max(1, M - len(tail))), replace=False)
+    return np.unique(np.concatenate([head, tail]))
+
+
+def test_config5_ragged_ffn_sampled_rows(rt, nb):
+    """Full-size M (sum of 32 lengths) in the launch configuration the benchmark
+    times; the oracle evaluates the residue region (last 512 rows) plus random
+    rows, which row independence makes exact.  FFN2 is teacher-forced with the
+    GPU's own bf16 FFN1 output."""
+    to_dev, _, from_dev, _ = _dev()
+    Ms = wl.config5_token_counts()
+    draws = [int(np.argmin(Ms)), int(np.argsort(Ms)[len(Ms) // 2]), int(np.argmax(Ms))]
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    dw1, db1, dw2, db2 = to_dev(w1), to_dev(b1), to_dev(w2), to_dev(b2)
+    rng = np.random.default_rng(55)
+    for d in draws:
+        M = int(Ms[d])
+        x = wl.activations(5, d, M, K1)
+        h = rt.dense(to_dev(x), dw1, db1, EPI[e1])
+        y = rt.dense(h, dw2, db2, EPI[e2])
+        assert tuple(h.shape) == (M, N1) and tuple(y.shape) == (M, N2)
+        rows = _sampled_rows(M, 256, 96, rng)
+        hg = from_dev(h)
+        ref_h = oracle.dense(x.f32[rows], w1.f32, b1.f32, e1)
+        assert _err(hg[rows], ref_h) <= TOL, ("ffn1", M)
+        ref_y = oracle.dense(hg[rows], w2.f32, b2.f32, e2)
+        assert _err(from_dev(y)[rows], ref_y) <= TOL, ("ffn2", M)
+
+
+def test_config5_residue_sweep_2048_plus_r(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    dw1, db1, dw2, db2 = to_dev(w1), to_dev(b1), to_dev(w2), to_dev(b2)
+    Mmax = 2048 + 255
+    x = wl.activations(5, 999, Mmax, K1)
+    xd = to_dev(x)
+    rng = np.random.default_rng(56)
+    fixed = np.sort(rng.choice(2048 - 64, size=48, replace=False))
+    rows_all = np.concatenate([fixed, np.arange(2048 - 64, Mmax)])
+    ref_h_all = oracle.dense(x.f32[rows_all], w1.f32, b1.f32, e1)
+    pos = {int(r): i for i, r in enumerate(rows_all)}
+    for r in range(0, 256):
+        M = 2048 + r
+        h = rt.dense(xd[:M], dw1, db1, EPI[e1])
+        rows = rows_all[rows_all < M]
+        idx = [pos[int(v)] for v in rows]
+        hg = from_dev(h)
+        assert _err(hg[rows], ref_h_all[idx]) <= TOL, ("ffn1", M)
+        if r % 16 in (0, 1, 15):  # FFN2 needs a fresh oracle evaluation per M (teacher forcing)
+            y = rt.dense(h, dw2, db2, EPI[e2])
+            sub = rows[-40:]
+            ref_y = oracle.dense(hg[sub], w2.f32, b2.f32, e2)
+            assert _err(from_dev(y)[sub], ref_y) <= TOL, ("ffn2", M)
+
+
+# ------------------------------------------------------------------ config 2
+def test_lstm_teacher_forced_steps(rt, nb):
+    """Per step both sides get identical inputs: the GPU's own bf16 h and f32 c."""
+    to_dev, f32_to_dev, from_dev, _ = _dev()
+    lw = wl.config2_weights()
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    H = wl.LSTM_H
+    plan = [(1, 128), (7, 128), (16, 6), (17, 6), (33, 6), (48, 4), (64, 6)]
+    plan += [(int(b), 3) for b in wl.config2_batches()[:6]]
+    for seq, (B, steps) in enumerate(plan):
+        xs = wl.config2_inputs(seq, B, steps)
+        h = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
+        c = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+        for t in range(steps):
+            xt = wl.BF16Array(xs.bits[t], xs.f32[t])
+            h_in, c_in = from_dev(h), from_dev(c)
+            h2, c2 = rt.lstm_step(to_dev(xt), h, dw, db, c)
+            assert tuple(h2.shape) == (B, H) and tuple(c2.shape) == (B, H)
+            ref_h, ref_c = oracle.lstm_step(xt.f32, h_in, lw.w.f32, lw.b.f32, c_in)
+            assert _err(from_dev(c2), ref_c) <= TOL, ("c", B, t)
+            assert _err(from_dev(h2), ref_h) <= TOL, ("h", B, t)
+            h, c = h2, c2
+
+
+def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
+    to_dev, f32_to_dev, from_dev, _ = _dev()
+    H, Ix, B = 64, 40, 21
+    rng = np.random.default_rng(8)
+    x, h0 = wl.uniform_bf16(rng, (B, Ix)), wl.uniform_bf16(rng, (B, H))
+    c0 = wl.uniform_bf16(rng, (B, H)).f32
+    zero_w = wl.BF16Array(np.zeros((4 * H, Ix + H), np.uint16), np.zeros((4 * H, Ix + H), np.float32))
+    zb = np.zeros((4 * H,), np.float32)
+    bz = wl.BF16Array(wl.f32_to_bf16_bits(zb), zb)
+    # zero weights: c halves every step, exactly; c_out aliases c_prev
+    c = f32_to_dev(c0)
+    h = to_dev(h0)
+    for t in range(1, 6):
+        h, c = rt.lstm_step(to_dev(x), h, to_dev(zero_w), to_dev(bz), c, c_out=c)
+        assert np.array_equal(from_dev(c), np.ldexp(c0, -t))
+        assert np.max(np.abs(from_dev(h) - 0.5 * np.tanh(np.ldexp(c0, -t)))) < 4e-3
+    # forget gate open, input gate shut: the state is carried
+    bf = zb.copy()
+    bf[H:2 * H] = 30.0
+    bf[0:H] = -30.0
+    bb = wl.BF16Array(wl.f32_to_bf16_bits(bf), bf)
+    h, c = rt.lstm_step(to_dev(x), to_dev(h0), to_dev(zero_w), to_dev(bb), f32_to_dev(c0))
+    assert np.max(np.abs(from_dev(c) - c0)) < 1e-6
+    # ragged H (not a multiple of 4 units per workgroup is impossible: H % 8 == 0), ragged B
+    for (B2, H2, Ix2) in [(5, 8, 8), (70, 24, 16), (3, 512, 0)]:
+        rng2 = np.random.default_rng(B2)
+        xx = wl.uniform_bf16(rng2, (B2, Ix2))
+        hh = wl.uniform_bf16(rng2, (B2, H2))
+        ww = wl.normal_bf16(rng2, (4 * H2, Ix2 + H2), std=0.2)
+        bias = wl.uniform_bf16(rng2, (4 * H2,))
+        cc = wl.uniform_bf16(rng2, (B2, H2)).f32
+        xdev = to_dev(xx) if Ix2 else torch.zeros((B2, 0), dtype=torch.bfloat16, device="cuda")
+        hg, cg = rt.lstm_step(xdev, to_dev(hh), to_dev(ww), to_dev(bias), f32_to_dev(cc))
+        rh, rc = oracle.lstm_step(xx.f32.reshape(B2, Ix2), hh.f32, ww.f32, bias.f32, cc)
+        assert _err(from_dev(cg), rc) <= TOL and _err(from_dev(hg), rh) <= TOL, (B2, H2, Ix2)
+
+
+# ------------------------------------------------------------------ config 4
+def test_attention_chain(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    Ls = sorted(set([1, 2, 7, 8, 63, 64, 65, 129, 200, 512] + [int(v) for v in wl.config4_lengths()[:4]]))
+    for d, L in enumerate(Ls):
+        q, k, v = wl.config4_qkv(d, L)
+        s, p, o = rt.attention(to_dev(q), to_dev(k), to_dev(v))
+        assert tuple(s.shape) == (12, L, L) and tuple(p.shape) == (12, L, L) and tuple(o.shape) == (12, L, 64)
+        rs, rp, ro = oracle.attention(q.f32, k.f32, v.f32)
+        assert _err(from_dev(s), rs) <= TOL, ("S", L)
+        assert _err(from_dev(p), rp) <= TOL, ("P", L)
+        assert _err(from_dev(o), ro) <= TOL, ("O", L)
+        # teacher-forced second batch_matmul: the oracle applied to the GPU's own bf16 P
+        ro2 = oracle.batch_matmul(from_dev(p), v.f32, False, 1.0)
+        assert _err(from_dev(o), ro2) <= TOL, ("O|P", L)
+        if L == 1:
+            assert np.array_equal(from_dev(p), np.ones((12, 1, 1), np.float32))
+            assert np.array_equal(from_dev(o), v.f32)
+
+
+def test_batch_matmul_general_shapes(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(9)
+    for (T, M, N, K, trans_b) in [(3, 70, 130, 64, True), (2, 300, 72, 136, True), (1, 5, 3, 7, True),
+                                  (4, 33, 64, 33, False), (2, 129, 40, 257, False), (12, 512, 512, 64, True)]:
+        a = wl.uniform_bf16(rng, (T, M, K))
+        b = wl.uniform_bf16(rng, (T, N, K) if trans_b else (T, K, N))
+        for od in (nb.BF16, nb.F32):
+            c = rt.batch_matmul(to_dev(a), to_dev(b), trans_b, 0.125, od)
+            ref = oracle.batch_matmul(a.f32, b.f32, trans_b, 0.125)
+            assert _err(from_dev(c), ref) <= TOL, (T, M, N, K, trans_b, od)
+
+
+def test_softmax_rows_on_gpu(rt, nb):
+    _, f32_to_dev, from_dev, _ = _dev()
+    rng = np.random.default_rng(10)
+    for rows, cols in [(1, 1), (5, 3), (12 * 7, 7), (12 * 65, 65), (100, 512), (3, 1000)]:
+        s = (8 * (2 * rng.random((rows, cols)) - 1)).astype(np.float32)
+        p = from_dev(rt.softmax_rows(f32_to_dev(s)))
+        ref = oracle.softmax_rows(s)
+        assert _err(p, ref) <= TOL
+        assert np.max(np.abs(p.sum(-1) - 1)) < 2e-2  # bf16 rounding of each term
+
+
+# ------------------------------------------------------------------ error paths on the device side
+def test_errors_leave_outputs_untouched(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(11)
+    x, w, b = wl.uniform_bf16(rng, (9, 128)), wl.uniform_bf16(rng, (64, 128)), wl.uniform_bf16(rng, (64,))
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    y = torch.full((9, 64), 5.0, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(nb.NimbleError) as e:  # K mismatch: the deferred type check fires, nothing runs
+        rt.dense(xd, to_dev(wl.uniform_bf16(rng, (64, 120))), bd, out=y)
+    assert e.value.code == -3
+    with pytest.raises(nb.NimbleError) as e:  # misaligned output pointer
+        nb.nimble_dense_dyn(xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr() + 2, 9, 64, 128, 1)
+    assert e.value.code == -5
+    with pytest.raises(nb.NimbleError) as e:
+        nb.nimble_dense_dyn(xd.data_ptr(), wd.data_ptr(), 0, y.data_ptr(), 9, 64, 128, 1)
+    assert e.value.code == -1
+    torch.cuda.synchronize()
+    assert np.all(from_dev(y) == 5.0)
+    # M = 0: legal, nothing launched, shape (0, N)
+    y0 = rt.dense(xd[:0], wd, bd)
+    assert tuple(y0.shape) == (0, 64)
+    rt.dense(xd, wd, bd, out=y)
+    assert _err(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias")) <= TOL

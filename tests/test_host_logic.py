@@ -1,0 +1,183 @@
+"""Host side of the C ABI (no GPU): the library loads and exports every symbol
+the header declares; shape functions, storage sizes, the residue split and the
+dispatch table agree with the oracle and with their own invariants."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2006_03031_amd as nb
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+TILED = {2: (32, 128), 3: (64, 128), 4: (128, 128), 5: (256, 128), 6: (256, 256)}
+
+
+def _golden_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [[c.strip() for c in l.split("|")] for l in f if l.strip() and not l.startswith("#")]
+
+
+def test_library_exports_every_declared_symbol():
+    lib = nb.load()
+    names = nb.exported_symbols()
+    assert {"nimble_dense_shape", "nimble_dense_dyn", "nimble_batch_matmul_dyn",
+            "nimble_lstm_gates_dyn"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None, name
+    assert os.path.basename(nb.library_path()) == "libnimble_hip.so"
+
+
+def test_dense_shape_matches_oracle_for_every_M():
+    for M in range(0, 514):
+        got = nb.nimble_dense_shape((M, 1024), (4096, 1024))
+        assert got == oracle.dense_shape((M, 1024), (4096, 1024)) == (M, 4096)
+
+
+def test_dense_shape_outputs_are_int64_and_untouched_on_error():
+    lib = nb.load()
+    xs = (ctypes.c_int64 * 2)(7, 128)
+    ws = (ctypes.c_int64 * 2)(64, 127)
+    out = (ctypes.c_int64 * 2)(-5, -6)
+    assert ctypes.sizeof(out) == 16  # a rank-2 shape is 16 bytes (Appendix A)
+    assert lib.nimble_dense_shape(xs, 2, ws, 2, out) == -3
+    assert (out[0], out[1]) == (-5, -6)
+    assert "K" in nb.last_error()
+    ws[1] = 128
+    assert lib.nimble_dense_shape(xs, 2, ws, 2, out) == 0 and (out[0], out[1]) == (7, 64)
+    assert lib.nimble_dense_shape(xs, 3, ws, 2, out) == -2
+    assert lib.nimble_dense_shape(None, 2, ws, 2, out) == -1
+    xs[0] = -1
+    assert lib.nimble_dense_shape(xs, 2, ws, 2, out) == -8
+
+
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_batch_matmul_shape_matches_oracle(trans_b):
+    for L in (0, 1, 7, 64, 65, 512):
+        a = (12, L, 64) if trans_b else (12, L, L)
+        b = (12, L, 64)
+        assert nb.batch_matmul_shape(a, b, trans_b) == oracle.batch_matmul_shape(a, b, trans_b)
+    bad = [((12, 5, 64), (11, 5, 64)), ((12, 5, 64), (12, 9, 63) if trans_b else (12, 63, 9))]
+    for a, b in bad:
+        with pytest.raises(nb.NimbleError) as e:
+            nb.batch_matmul_shape(a, b, trans_b)
+        assert e.value.code == -3
+        with pytest.raises(oracle.OracleShapeError):
+            oracle.batch_matmul_shape(a, b, trans_b)
+    with pytest.raises(nb.NimbleError) as e:
+        nb.batch_matmul_shape((5, 64), (12, 9, 64), trans_b)
+    assert e.value.code == -2
+
+
+def test_lstm_shape_matches_oracle():
+    for B in (0, 1, 16, 33, 64):
+        args = ((B, 512), (B, 512), (B, 512), (2048, 1024))
+        assert nb.lstm_shape(*args) == oracle.lstm_shape(*args) == ((B, 512), (B, 512))
+    for bad in [((3, 512), (4, 512), (3, 512), (2048, 1024)), ((3, 512), (3, 512), (3, 511), (2048, 1024)),
+                ((3, 512), (3, 512), (3, 512), (2047, 1024)), ((3, 512), (3, 512), (3, 512), (2048, 1023))]:
+        with pytest.raises(nb.NimbleError) as e:
+            nb.lstm_shape(*bad)
+        assert e.value.code == -3
+
+
+def test_storage_bytes_golden_and_oracle():
+    itemsize_to_dtype = {4: nb.F32}
+    for shape, itemsize, nbytes, align in _golden_rows("storage_sizes.txt"):
+        dims = [int(d) for d in shape.split(",")]
+        if int(itemsize) in itemsize_to_dtype:
+            assert nb.storage_bytes(dims, itemsize_to_dtype[int(itemsize)]) == int(nbytes)
+        assert nb.storage_alignment() == int(align)
+    for shape in [(0, 4096), (1, 128), (8208, 4096), (12, 512, 512), ()]:
+        assert nb.storage_bytes(shape, nb.BF16) == oracle.storage_bytes(shape, 2)
+        assert nb.storage_bytes(shape, nb.F32) == oracle.storage_bytes(shape, 4)
+    with pytest.raises(nb.NimbleError):
+        nb.storage_bytes((3, -1), nb.BF16)
+    with pytest.raises(nb.NimbleError):
+        nb.storage_bytes((3, 4), 7)
+
+
+def test_residue_split_matches_oracle_and_paper_example():
+    for tile, copies, rmin, rmax in ([int(v) for v in r] for r in _golden_rows("residue_tile8.txt")):
+        rs = {nb.residue_split(x, tile)[1] for x in range(0, 4 * tile)}
+        assert rs == set(range(rmin, rmax + 1)) and len(rs) == copies
+    for tile in (8, 16, 32, 64, 128, 256):
+        for x in range(0, 2 * tile + 2):
+            assert nb.residue_split(x, tile) == oracle.residue_split(x, tile)
+    with pytest.raises(nb.NimbleError):
+        nb.residue_split(3, 0)
+
+
+@pytest.mark.parametrize("variant", sorted(TILED))
+def test_plan_residue_identity_for_every_tiled_variant(variant):
+    bm, bn = TILED[variant]
+    for N, K in ((4096, 1024), (200, 72)):
+        for M in range(1, 2 * bm + 2):
+            p = nb.dense_plan(M, N, K, force_variant=variant)
+            assert (p.variant, p.bm, p.bn) == (variant, bm, bn)
+            assert p.k * bm + p.r == M and 0 <= p.r < bm
+            assert (p.k, p.r) == oracle.residue_split(M, bm)
+            tiles_m = p.k + (1 if p.r else 0)
+            assert tiles_m * bm >= M > (tiles_m - 1) * bm
+            assert p.grid[0] == tiles_m * -(-N // bn) and p.grid[2] == 1
+            expect_residue = int(p.r != 0 or N % bn != 0 or K % 64 != 0)
+            assert p.residue_copy == expect_residue
+            assert p.workspace_bytes == 0
+
+
+def test_auto_dispatch_table():
+    # small M streams the weights; large M goes to big tiles; ragged K falls back
+    for M in range(1, 65):
+        p = nb.dense_plan(M, 2048, 1024)
+        assert p.name == "skinny16" and p.k * 16 + p.r == M
+        assert p.grid[0] == 128 and p.grid[1] == 1
+    assert nb.dense_plan(65, 2048, 1024).name.startswith("t")
+    assert nb.dense_plan(8192, 4096, 1024).name in ("t256x256", "t256x128")
+    assert nb.dense_plan(8192, 4096, 1024).residue_copy == 0
+    assert nb.dense_plan(8193, 4096, 1024).residue_copy == 1
+    assert nb.dense_plan(100, 128, 100).name == "generic"
+    assert nb.dense_plan(100, 128, 0).name == "generic"
+    for M in range(65, 1200, 7):
+        p = nb.dense_plan(M, 3072, 768)
+        assert p.k * p.bm + p.r == M
+
+
+def test_plan_rejects_bad_arguments():
+    for args in [(-1, 128, 128), (5, -1, 128), (5, 128, -8)]:
+        with pytest.raises(nb.NimbleError) as e:
+            nb.dense_plan(*args)
+        assert e.value.code == -8
+    with pytest.raises(nb.NimbleError):
+        nb.dense_plan(5, 128, 128, epilogue=9)
+    with pytest.raises(nb.NimbleError):
+        nb.dense_plan(5, 128, 128, force_variant=99)
+    with pytest.raises(nb.NimbleError):
+        nb.dense_plan(5, 128, 100, force_variant=4)  # tiled needs K % 8 == 0
+    with pytest.raises(nb.NimbleError):
+        nb.lstm_plan(4, 510, 512)
+
+
+def test_lstm_plan():
+    for B in range(0, 130):
+        p = nb.lstm_plan(B, 512, 512)
+        assert p.k * 16 + p.r == B and p.grid[0] == 128 and p.grid[1] == -(-B // 64)
+
+
+def test_device_entry_points_validate_before_touching_the_gpu():
+    # every one of these must be refused on the host (no GPU in this process)
+    lib = nb.load()
+    assert lib.nimble_dense_dyn(None, None, None, None, 4, 128, 128, 1, 0, -1, None, 0, None) == -1
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, -4, 128, 128, 1, 0, -1, None, 0, None) == -8
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 7, 0, -1, None, 0, None) == -8
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 1, 5, -1, None, 0, None) == -4
+    assert lib.nimble_dense_dyn(16, 32, 48, 68, 4, 128, 128, 1, 0, -1, None, 0, None) == -5
+    assert lib.nimble_dense_dyn(16, 32, None, 64, 4, 128, 128, 1, 0, -1, None, 0, None) == -1
+    # M = 0 is a legal instantiation of the dynamic dimension: nothing to do
+    assert lib.nimble_dense_dyn(None, None, None, None, 0, 128, 128, 1, 0, -1, None, 0, None) == 0
+    assert lib.nimble_batch_matmul_dyn(None, None, None, 12, 0, 0, 64, 1, 0.125, 1, None, 0, None) == 0
+    assert lib.nimble_batch_matmul_dyn(16, 32, 50, 12, 4, 4, 64, 1, 0.125, 1, None, 0, None) == -5
+    assert lib.nimble_softmax_rows_dyn(None, None, 0, 5, None) == 0
+    assert lib.nimble_softmax_rows_dyn(None, None, 3, 5, None) == -1
+    assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 0, 512, 512, None, 0, None) == 0
+    assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 32, 3, 512, 512, None, 0, None) == -8  # h_out aliases h_prev
+    assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 3, 511, 512, None, 0, None) == -8
