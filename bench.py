@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamic-M dense hot path on one MI355X.
+
+Headline workload: the BERT-large shaped FFN at a ragged total token count
+(M = sum of 32 sequence lengths, each uniform in 1..512; 64 seeded draws).  One
+step is one pass of the whole path over one draw: read the run-time shape,
+shape function, allocate the outputs from it, dispatch on M, and the two dense
+kernels (1024->4096 with bias+GELU, 4096->1024 with bias).  Inputs and weights
+are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def _to_dev(arr):
+    import numpy as np
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(arr.bits).view(np.int16).copy())
+    return t.view(torch.bfloat16).cuda()
+
+
+def _traffic_note():
+    """HBM bytes per dense launch measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy kernel of known size); recorded under profiles/."""
+    path = os.path.join(ROOT, "profiles", "dense_config5_traffic.json")
+    if os.path.exists(path):
+        try:
+            return json.load(open(path)).get("hbm_bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def bench_config5(steps: int, warmup: int):
+    import numpy as np
+    import torch
+
+    import paper_2006_03031_amd as nb
+    import workloads as wl
+    from paper_2006_03031_amd import runtime as rt
+
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    epi = {"bias": nb.EPI_BIAS, "bias_gelu": nb.EPI_BIAS_GELU_ERF}
+    Ms = [int(m) for m in wl.config5_token_counts()]
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    dw1, db1, dw2, db2 = _to_dev(w1), _to_dev(b1), _to_dev(w2), _to_dev(b2)
+    x_all = _to_dev(wl.activations(5, 0, max(Ms), K1))  # a draw of M tokens reads the first M rows
+    torch.cuda.synchronize()
+
+    def step(i, events=None):
+        M = Ms[i % len(Ms)]
+        x = x_all[:M]
+        # shape function -> allocation -> dispatch -> kernel, twice
+        if events is not None:
+            s0, s1, s2, s3 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+            s0.record()
+            h = rt.dense(x, dw1, db1, epi[e1])
+            s1.record()
+            s2.record()
+            y = rt.dense(h, dw2, db2, epi[e2])
+            s3.record()
+            events.append((M, s0, s1, s2, s3))
+        else:
+            h = rt.dense(x, dw1, db1, epi[e1])
+            y = rt.dense(h, dw2, db2, epi[e2])
+        return y
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_flops = sum(2.0 * M * (N1 * K1 + N2 * K2) for M, *_ in events)
+    elapsed = t1 - t0
+    # per-launch durations of the dense kernels from HIP events on the launch stream
+    k_flops = k_ms = 0.0
+    launches = 0
+    for M, s0, s1, s2, s3 in events:
+        k_ms += s0.elapsed_time(s1) + s2.elapsed_time(s3)
+        k_flops += 2.0 * M * N1 * K1 + 2.0 * M * N2 * K2
+        launches += 2
+    achieved = k_flops / (k_ms * 1e-3) / 1e12
+    plans = sorted({nb.dense_plan(M, N1, K1).name for M in Ms} | {nb.dense_plan(M, N2, K2).name for M in Ms})
+    roofline = {
+        "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": _traffic_note(),
+        "kernel": "gemm_tile_kernel (" + ",".join(plans) + ")", "launches": launches,
+        "avg_launch_us": round(k_ms * 1e3 / launches, 2),
+        "flops_per_launch": round(k_flops / launches),
+    }
+    return {
+        "value": total_flops / elapsed / 1e12, "ms_per_step": elapsed * 1e3 / steps, "roofline": roofline,
+        "mean_M": sum(M for M, *_ in events) / len(events),
+    }
+
+
+def small_m_probe():
+    """Secondary figures (not the headline): weight-streaming dense at M <= 16 with
+    weights rotated through 512 MB so that they come from HBM, and one LSTM step."""
+    import numpy as np
+    import torch
+
+    import paper_2006_03031_amd as nb
+    import workloads as wl
+    from paper_2006_03031_amd import runtime as rt
+
+    out = {}
+    N, K = 4096, 1024
+    sets = 64  # 64 x 8 MB = 512 MB of distinct weights
+    w = torch.empty((sets, N, K), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    b = torch.zeros((N,), dtype=torch.bfloat16, device="cuda")
+    for M in (1, 16):
+        x = torch.empty((M, K), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        for i in range(sets):
+            rt.dense(x, w[i], b, nb.EPI_BIAS, out=y)
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 4 * sets
+        s.record()
+        for i in range(reps):
+            rt.dense(x, w[i % sets], b, nb.EPI_BIAS, out=y)
+        e.record()
+        torch.cuda.synchronize()
+        us = s.elapsed_time(e) * 1e3 / reps
+        nbytes = N * K * 2 + N * 2 + M * K * 2 + M * N * 2
+        out[f"dense_{K}x{N}_M{M}_rotating"] = {"us_per_call": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                                 "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4)}
+    del w
+    lw = wl.config2_weights()
+    dw, db = _to_dev(lw.w), _to_dev(lw.b)
+    for B in (1, 16, 64):
+        x = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        h0 = torch.zeros((B, 512), dtype=torch.bfloat16, device="cuda")
+        h1 = torch.zeros_like(h0)
+        c = torch.zeros((B, 512), dtype=torch.float32, device="cuda")
+        for _ in range(16):
+            rt.lstm_step(x, h0, dw, db, c, h_out=h1, c_out=c)
+            h0, h1 = h1, h0
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(128):
+            rt.lstm_step(x, h0, dw, db, c, h_out=h1, c_out=c)
+            h0, h1 = h1, h0
+        e.record()
+        torch.cuda.synchronize()
+        us = s.elapsed_time(e) * 1e3 / 128
+        nbytes = 2048 * 1024 * 2 + 4096 + 7168 * B
+        out[f"lstm_step_B{B}_warm"] = {"us_per_step": round(us, 2), "eff_GBps": round(nbytes / us / 1e3, 1)}
+    return out
+
+
+def cpu_baseline():
+    """The oracle as it stands, timed on the host cores on a bounded sample of the
+    same workload: the median-M and the largest-M draw, both FFN GEMMs."""
+    import numpy as np
+
+    import oracle
+    import workloads as wl
+
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    Ms = wl.config5_token_counts()
+    order = np.argsort(Ms)
+    draws = [int(order[len(Ms) // 2]), int(order[-1])]
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    flops = 0.0
+    t = 0.0
+    for d in draws:
+        M = int(Ms[d])
+        x = wl.activations(5, d, M, K1).f32
+        t0 = time.perf_counter()
+        h = oracle.dense(x, w1.f32, b1.f32, e1)
+        y = oracle.dense(h, w2.f32, b2.f32, e2)
+        t += time.perf_counter() - t0
+        flops += 2.0 * M * (N1 * K1 + N2 * K2)
+        del h, y
+    return {"value": round(flops / t / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"draws with M={[int(Ms[d]) for d in draws]} (median and largest), "
+                                        f"FFN1+FFN2, {flops / 1e9:.0f} GFLOP in {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2006_03031_amd as nb
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    nb.load()
+    torch.cuda.set_device(0)
+
+    res = bench_config5(args.steps, args.warmup)
+    line = {
+        "metric": "dynamic-M dense TFLOP/s (bf16) over M sweep; % of MFMA/HBM roofline",
+        "value": round(res["value"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(res["ms_per_step"], 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "BERT-large FFN (1024->4096 bias+GELU, 4096->1024 bias) at ragged token count "
+                               "M = sum of 32 lengths U{1..512}, 64 seeded draws, one draw per step",
+                   "mean_M": round(res["mean_M"], 1), "weights": "bf16 N(0,0.02)",
+                   "activations": "bf16 U[-1,1)", "accumulate": "f32"},
+        "roofline": res["roofline"],
+    }
+    if not args.no_extra:
+        line["extra"] = small_m_probe()
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

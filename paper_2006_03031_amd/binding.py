@@ -30,7 +30,8 @@ class _CPlan(ctypes.Structure):
                 ("bk", ctypes.c_int32), ("k", ctypes.c_int64), ("r", ctypes.c_int32),
                 ("residue_copy", ctypes.c_int32), ("split_k", ctypes.c_int32),
                 ("grid", ctypes.c_uint32 * 3), ("block", ctypes.c_uint32),
-                ("workspace_bytes", ctypes.c_uint64)]
+                ("workspace_bytes", ctypes.c_uint64), ("split_rows", ctypes.c_int64),
+                ("residue_variant", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 @dataclass
@@ -47,6 +48,8 @@ class Plan:
     grid: Tuple[int, int, int]
     block: int
     workspace_bytes: int
+    split_rows: int = 0
+    residue_variant: int = -1
 
 
 _lib = None
@@ -167,7 +170,8 @@ def variant_name(v: int) -> Optional[str]:
 
 def _plan(c: _CPlan) -> Plan:
     return Plan(c.variant, variant_name(c.variant) or "?", c.bm, c.bn, c.bk, c.k, c.r, c.residue_copy,
-                c.split_k, (c.grid[0], c.grid[1], c.grid[2]), c.block, c.workspace_bytes)
+                c.split_k, (c.grid[0], c.grid[1], c.grid[2]), c.block, c.workspace_bytes, c.split_rows,
+                c.residue_variant)
 
 
 def dense_plan(M: int, N: int, K: int, epilogue: int = EPI_BIAS, out_dtype: int = BF16,

@@ -29,9 +29,9 @@ const VariantInfo kVariants[NIMBLE_VAR_COUNT] = {
     {"skinny16", 16, 16, 32, 256},
     {"t32x128", 32, 128, 64, 256},
     {"t64x128", 64, 128, 64, 256},
-    {"t128x128", 128, 128, 64, 256},
-    {"t256x128", 256, 128, 64, 256},
-    {"t256x256", 256, 256, 64, 256},
+    {"t128x128", 128, 128, 32, 256},
+    {"t256x128", 256, 128, 32, 512},
+    {"t256x256", 256, 256, 32, 512},
 };
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -39,24 +39,31 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Number of compute units of one MI355X.
 static const int64_t kCUs = 256;
 
-// Relative cost of one macro tile per unit of K: area divided by how well the
-// variant keeps the matrix cores busy (measured per-variant efficiencies).
-static double tile_cost(int variant) {
+// Estimated time of one macro tile, in arbitrary units: the tile's area times
+// (K plus a fixed per-tile overhead expressed in units of K: pipeline fill and
+// the epilogue, which is larger with GELU), divided by how well the variant
+// keeps the matrix cores busy in steady state (measured per variant at
+// M = 8192 on the BERT-large FFN shapes).
+static double tile_cost(int variant, int64_t K, int epilogue) {
+  double eff;
   switch (variant) {
-    case NIMBLE_VAR_T32x128: return 32.0 * 128 / 0.25;
-    case NIMBLE_VAR_T64x128: return 64.0 * 128 / 0.40;
-    case NIMBLE_VAR_T128x128: return 128.0 * 128 / 0.70;
-    case NIMBLE_VAR_T256x128: return 256.0 * 128 / 0.90;
-    case NIMBLE_VAR_T256x256: return 256.0 * 256 / 1.00;
+    case NIMBLE_VAR_T32x128: eff = 0.30; break;
+    case NIMBLE_VAR_T64x128: eff = 0.50; break;
+    case NIMBLE_VAR_T128x128: eff = 0.87; break;
+    case NIMBLE_VAR_T256x128: eff = 0.97; break;
+    case NIMBLE_VAR_T256x256: eff = 1.00; break;
     default: return 1e30;
   }
+  const double k0 = (epilogue == NIMBLE_EPI_BIAS_GELU_ERF) ? 256.0 : 128.0;
+  return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) / eff;
 }
 
 bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K) {
   (void)M;
   (void)N;
   if (variant < NIMBLE_VAR_T32x128 || variant > NIMBLE_VAR_T256x256) return false;
-  return K > 0 && K % 8 == 0;  // rows must stay 16-byte aligned
+  // rows must stay 16-byte aligned; per-lane byte offsets inside a tile are 32-bit
+  return K > 0 && K % 8 == 0 && K <= (1ll << 22);
 }
 
 static void fill_tiled(nimble_plan* p, int variant, int64_t batch, int64_t M, int64_t N, int64_t K) {
@@ -76,28 +83,63 @@ static void fill_tiled(nimble_plan* p, int variant, int64_t batch, int64_t M, in
   p->workspace_bytes = 0;
 }
 
-// Choose the tiled variant whose estimated time is least.  The busiest compute
-// unit executes ceil(tiles / CUs) tiles, so a dynamic M just past a tile
-// boundary can cost a whole extra tile per CU with big tiles; smaller tiles
-// quantise more finely but run the matrix cores less efficiently.
-static int choose_tiled(int64_t batch, int64_t M, int64_t N, int64_t K) {
+// One unit of tile_cost in microseconds (a 256x256 tile at K = 1024 with GELU takes about 42 us).
+static const double kUsPerUnit = 5.1e-7;
+// Gap between two dependent launches on one stream, microseconds.
+static const double kLaunchGapUs = 4.0;
+
+// Estimated time of one launch of tiled variant v over `rows` rows, microseconds.  The
+// tiles run in rounds of one per compute unit.  A full round runs at the chip's
+// power-limited rate; the last, partial round runs faster per tile the fewer units it
+// occupies (measured: about 0.62 of the full-round time when a handful of units are
+// busy, 0.72 at half the chip).  So a dynamic M just past a tile boundary costs most of
+// an extra round with big tiles, while smaller tiles quantise more finely but run the
+// matrix cores less efficiently.
+static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue) {
+  const VariantInfo& vi = kVariants[v];
+  const int64_t tiles = batch * ceil_div(rows, vi.bm) * ceil_div(N, vi.bn);
+  const double t_full = tile_cost(v, K, epilogue) * kUsPerUnit;
+  const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
+  double us = (double)full_rounds * t_full;
+  if (rem > 0) {
+    const double occ = (double)rem / (double)kCUs;
+    us += t_full * (0.62 + 0.38 * occ * occ);
+  }
+  return us;
+}
+
+// The weight-streaming kernel is bound by launch latency and by reading W once.
+static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
+  return 6.0 + (double)ceil_div(rows, 64) * (double)N * (double)K * 2.0 / 3.0e6;
+}
+
+static int best_tiled(int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue, double* cost_us) {
   int best = -1;
   double best_cost = 0;
   for (int v = NIMBLE_VAR_T32x128; v <= NIMBLE_VAR_T256x256; ++v) {
-    if (!tiled_variant_ok(v, M, N, K)) continue;
-    const VariantInfo& vi = kVariants[v];
-    if (v > NIMBLE_VAR_T32x128 && M <= kVariants[v - 1].bm) break;  // tile taller than needed
-    const int64_t tiles = batch * ceil_div(M, vi.bm) * ceil_div(N, vi.bn);
-    const double cost = (double)ceil_div(tiles, kCUs) * tile_cost(v);
+    if (!tiled_variant_ok(v, rows, N, K)) continue;
+    if (v > NIMBLE_VAR_T32x128 && rows <= kVariants[v - 1].bm) break;  // tile taller than needed
+    const double cost = tiled_cost_us(v, batch, rows, N, K, epilogue);
     if (best < 0 || cost < best_cost) {
       best = v;
       best_cost = cost;
     }
   }
+  if (cost_us) *cost_us = best_cost;
   return best;
 }
 
-int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int force_variant, nimble_plan* p) {
+// Best kernel for a few residue rows: the weight-streaming kernel up to 64 rows, else a small tile.
+static int best_for_residue(int64_t rows, int64_t N, int64_t K, int epilogue, double* cost_us) {
+  if (rows <= 64) {
+    *cost_us = skinny_cost_us(rows, N, K);
+    return NIMBLE_VAR_SKINNY16;
+  }
+  return best_tiled(1, rows, N, K, epilogue, cost_us);
+}
+
+int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int force_variant,
+               nimble_plan* p) {
   std::memset(p, 0, sizeof(*p));
   if (M < 0 || N < 0 || K < 0 || batch < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (M > (1ll << 30) || N > (1ll << 30) || K > (1ll << 30) || batch > 65535)
@@ -112,14 +154,38 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int force_variant
     return fail(NIMBLE_ERR_ARG, "unknown variant %d", variant);
 
   const bool aligned_k = (K > 0 && K % 8 == 0);
+  int64_t split_rows = 0;
+  int residue_variant = NIMBLE_VAR_AUTO;
   if (variant == NIMBLE_VAR_AUTO) {
     if (!aligned_k || M == 0 || N == 0) {
       variant = NIMBLE_VAR_GENERIC;
     } else if (M <= 64 && batch == 1) {
       variant = NIMBLE_VAR_SKINNY16;
     } else {
-      variant = choose_tiled(batch, M, N, K);
+      double single_us = 0;
+      variant = best_tiled(batch, M, N, K, epilogue, &single_us);
       if (variant < 0) variant = NIMBLE_VAR_GENERIC;
+      // Alternative: x = bm*k + r as two launches.  The k full tiles run the r = 0 copy of a
+      // big-tile variant (no bounds code, whole rounds of tiles), the r residue rows run a
+      // kernel built for few rows.  Taken when the estimate beats the best single launch.
+      if (variant != NIMBLE_VAR_GENERIC && batch == 1) {
+        double best_us = single_us;
+        for (int v = NIMBLE_VAR_T128x128; v <= NIMBLE_VAR_T256x256; ++v) {
+          const VariantInfo& vi = kVariants[v];
+          const int64_t k = M / vi.bm, r = M % vi.bm;
+          if (k == 0 || r == 0 || N % vi.bn != 0 || K % vi.bk != 0) continue;
+          double res_us = 0;
+          const int rv = best_for_residue(r, N, K, epilogue, &res_us);
+          if (rv < 0) continue;
+          const double us = tiled_cost_us(v, 1, k * vi.bm, N, K, epilogue) + kLaunchGapUs + res_us;
+          if (us < best_us) {
+            best_us = us;
+            variant = v;
+            split_rows = k * vi.bm;
+            residue_variant = rv;
+          }
+        }
+      }
     }
   }
 
@@ -159,7 +225,16 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int force_variant
   }
   if (!tiled_variant_ok(variant, M, N, K))
     return fail(NIMBLE_ERR_ARG, "variant %s cannot run K=%lld", kVariants[variant].name, (long long)K);
-  fill_tiled(p, variant, batch, M, N, K);
+  fill_tiled(p, variant, batch, split_rows > 0 ? split_rows : M, N, K);
+  if (split_rows > 0) {
+    // k and r describe the whole call; grid and residue_copy describe the first launch
+    p->k = M / p->bm;
+    p->r = (int32_t)(M % p->bm);
+    p->split_rows = split_rows;
+    p->residue_variant = residue_variant;
+  } else {
+    p->residue_variant = NIMBLE_VAR_AUTO;
+  }
   return NIMBLE_OK;
 }
 
@@ -265,7 +340,7 @@ int nimble_dense_plan(int64_t M, int64_t N, int64_t K, int epilogue, int out_dty
   if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
     return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
   if (dtype_size(out_dtype) == 0) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
-  return plan_dense(1, M, N, K, force_variant, plan);
+  return plan_dense(1, M, N, K, epilogue, force_variant, plan);
 }
 
 int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b,
@@ -275,13 +350,9 @@ int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int
   if (dtype_size(out_dtype) == 0) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
   if (!trans_b) {
     // b is (T,K,N): rows of b are not K-contiguous; the bounds-checked kernel reads it strided
-    return plan_dense(batch, M, N, K, NIMBLE_VAR_GENERIC, plan);
+    return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, plan);
   }
-  const int force = (batch > 1 || M > 64) ? NIMBLE_VAR_AUTO : NIMBLE_VAR_AUTO;
-  int rc = plan_dense(batch, M, N, K, force, plan);
-  if (rc == NIMBLE_OK && plan->variant == NIMBLE_VAR_SKINNY16 && batch != 1)
-    rc = plan_dense(batch, M, N, K, NIMBLE_VAR_GENERIC, plan);
-  return rc;
+  return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, plan);
 }
 
 int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {

@@ -19,7 +19,8 @@ void clear_error();
 bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
 
 // Dispatch table shared by dense (batch = 1) and batch_matmul.
-int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int force_variant, nimble_plan* p);
+int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int force_variant,
+               nimble_plan* p);
 
 // One C = epi(alpha * A.B^T + bias) problem as the kernels see it.  A is
 // [M,K] with row stride lda, B is [N,K] with row stride ldb (or, when

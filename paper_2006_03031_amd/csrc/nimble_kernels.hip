@@ -3,10 +3,16 @@
 // cores (v_mfma_f32_32x32x16_bf16 / v_mfma_f32_16x16x32_bf16), f32 epilogue.
 //
 // Kernel family
-//   gemm_tile_kernel<BM,BN,WGM,WGN,EDGE>  LDS-staged, double-buffered K tiles of 64.
-//       EDGE=false is the residue-0 copy: no bounds code at all.
-//       EDGE=true  is the residue copy: rows are clamped on load and masked on
-//       store in the last tile along M (and along N / K when those are ragged).
+//   gemm_ring_kernel<BM,BN,WGM,WGN,RESIDUE>  large tiles (128x128, 256x128, 256x256).
+//       Interior tiles: a ring of four 32-wide K stages filled by direct
+//       global->LDS loads (no register staging), 16x16x32 MFMA with the next
+//       stage's fragments read while the current stage multiplies, and an
+//       epilogue that transposes through LDS so that every store is a full
+//       128-byte line.  RESIDUE=false is the copy for r = 0: no bounds code at
+//       all.  RESIDUE=true is the copy for r != 0: workgroups whose tile touches
+//       an edge (decided once per workgroup) run a clamped and masked body.
+//   gemm_tile_kernel<BM,BN,WGM,WGN,RESIDUE>  small tiles (32x128, 64x128),
+//       register-staged double-buffered K tiles of 64, 32x32x16 MFMA.
 //   skinny_kernel<MT,LSTM>   M <= 64 per workgroup: the weights are streamed from
 //       HBM exactly once straight into MFMA operands, the four waves of a
 //       workgroup split K and reduce through LDS.  LSTM=true gathers the four
@@ -37,8 +43,23 @@ __device__ __forceinline__ u16 f2bf(float f) {
   return (u16)(u >> 16);
 }
 
+// erf(|x|) by the rational-times-Gaussian form of Abramowitz & Stegun 7.1.26
+// (|error| <= 1.5e-7), on the hardware exp2 and reciprocal: about a dozen
+// instructions where the library erff costs several times that, which matters
+// when the epilogue runs once per output element.
+// gelu(v) = v/2 (1 + erf(v / sqrt 2)) = v/2 + |v/2| erf(|v| / sqrt 2)
 __device__ __forceinline__ float gelu_erf(float v) {
-  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+  const float ax = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(v * v * -0.72134752044448170f);  // exp(-v^2 / 2)
+  const float r = fmaf(-p, e, 1.0f);                                       // erf(|v| / sqrt 2)
+  const float hv = 0.5f * v;
+  return fmaf(fabsf(hv), r, hv);
 }
 
 __device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
@@ -51,6 +72,34 @@ __device__ __forceinline__ float epilogue(float acc, float alpha, float bias, in
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Two float32 -> two bfloat16 (round to nearest even) in one v_cvt_pk_bf16_f32; lo in bits 0..15.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte
+// address lds_addr + 16 i (lds_addr is wave-uniform and goes through M0).  It is
+// tracked by vmcnt only; the caller waits with s_waitcnt vmcnt before a barrier
+// makes the data visible to the other waves.  Written as inline assembly so that
+// the compiler does not serialise it against LDS reads of the other ring slots.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_addr)
+               : "memory", "m0");
+}
+// Same, addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit per-lane
+// byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
+__device__ __forceinline__ void dma16_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase),
+               "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 
 // ---------------------------------------------------------------------------
 // Workgroup id -> macro tile.  Workgroups are handed to the 8 XCDs round robin;
@@ -75,17 +124,22 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
 // ---------------------------------------------------------------------------
 // LDS-tiled MFMA kernel.
 //   LDS tile layout: row-major rows of 64 bf16 (8 chunks of 16 bytes); chunk c
-//   of row r is stored at chunk slot c ^ (r & 7), which makes both the
-//   row-wise 16-byte writes and the column-of-rows 16-byte fragment reads
-//   conflict free.
+//   of row r is stored at chunk slot c ^ ((r >> 1) & 7).  The LDS serves a
+//   16-byte-per-lane access 16 lanes at a time over 64 banks (256 bytes), so 16
+//   consecutive rows at one logical chunk must land on 16 distinct 16-byte
+//   slots modulo 256 bytes: rows r and r+1 differ in bit 7 of the address, and
+//   the XOR spreads the 8 row pairs over the 8 chunk slots.  The row-wise
+//   writes (8 lanes per row) are conflict free under any such permutation.
 //   MFMA operand roles: the A operand (32 rows i) is a slab of B = weights
 //   (output features n), the B operand (32 columns j) is a slab of A =
 //   activations (rows m).  A lane then owns four consecutive n of one row m in
 //   every group of four accumulator registers, which gives packed stores.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, bool EDGE>
-__global__ void __launch_bounds__(WGM* WGN * 64)
-    gemm_tile_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+__device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int m0, const int n0,
+                                               uint4* smem) {
+  uint4(*As)[BM * 8] = reinterpret_cast<uint4(*)[BM * 8]>(smem);
+  uint4(*Bs)[BN * 8] = reinterpret_cast<uint4(*)[BN * 8]>(smem + 2 * BM * 8);
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -93,13 +147,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
   static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the workgroup");
   static_assert(TM >= 1 && TN >= 1, "wave tile too small");
   constexpr int ROWS_PER_PASS = NT / 8;
+  static_assert(ROWS_PER_PASS % 16 == 0, "the LDS swizzle needs passes of whole 16-row groups");
 
-  __shared__ __attribute__((aligned(16))) uint4 As[2][BM * 8];
-  __shared__ __attribute__((aligned(16))) uint4 Bs[2][BN * 8];
-
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int z = blockIdx.z;
   const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa;
   const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb;
@@ -112,7 +161,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
 
   // global -> LDS assignment: thread handles chunk (tid & 7) of rows (tid >> 3) + i * ROWS_PER_PASS
   const int ld_row = tid >> 3, ld_c = tid & 7;
-  const int ld_slot = ld_row * 8 + (ld_c ^ (ld_row & 7));  // ROWS_PER_PASS is a multiple of 8
+  const int ld_slot = ld_row * 8 + (ld_c ^ ((ld_row >> 1) & 7));  // ROWS_PER_PASS is a multiple of 16
   const u16* a_src[A_LD];
   const u16* b_src[B_LD];
 #pragma unroll
@@ -133,7 +182,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
   const int fr_a = (wm * WM + fr_row) * 8;
   const int fr_b = (wn * WN + fr_row) * 8;
   const int fr_half = lane >> 5;
-  const int fr_x = lane & 7;
+  const int fr_x = (lane >> 1) & 7;
 
   f32x16 acc[TN][TM];
 #pragma unroll
@@ -250,6 +299,243 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
       }
     }
   }
+}
+
+// RESIDUE=false is the copy for r = 0 (and N, K multiples of the tile): no
+// bounds code exists in it.  RESIDUE=true is the copy the dispatch function
+// picks for r != 0: only the workgroups whose tile touches an edge run the
+// clamped and masked body, decided once per workgroup; every interior tile
+// runs the same unchecked body as the r = 0 copy.
+template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
+__global__ void __launch_bounds__(WGM* WGN * 64)
+    gemm_tile_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+  __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  if (RESIDUE) {
+    const bool edge = (m0 + BM > g.M) || (n0 + BN > g.N) || ((g.K & 63) != 0) || ((g.ldc & 3) != 0);
+    if (edge) {
+      gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      return;
+    }
+  }
+  gemm_tile_body<BM, BN, WGM, WGN, false>(g, m0, n0, smem);
+}
+
+// ---------------------------------------------------------------------------
+// Interior body of the large tiles.
+//   LDS: a ring of S = 4 stages, each BM + BN rows of 32 bf16 (4 chunks of 16
+//   bytes); chunk c of row r sits at slot c ^ ((r >> 2) & 3), so that the 16
+//   rows one quarter-wave reads at one logical chunk cover all 64 banks.
+//   Every wave issues its share of each stage as 16-byte-per-lane direct
+//   global->LDS loads (a wave instruction fills 16 rows x 64 bytes = 1 KiB of
+//   contiguous LDS); the swizzle is applied on the global side by choosing
+//   which chunk a lane fetches.
+//   Step ks: wait until this wave's loads of stage ks+1 have landed, barrier
+//   (now every wave's have, and every wave has finished reading stage ks-1),
+//   refill the slot of stage ks-1 with stage ks+3, read the fragments of stage
+//   ks+1 into the second register set, run the MFMAs of stage ks.
+//   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
+//   activation rows (m); a lane ends up with 4 consecutive n of one row m.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, bool MEDGE>
+__device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
+                                               uint4* smem) {
+  constexpr int S = 4;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 16, TN = WN / 16;
+  constexpr int A_LD = BM * 4 / NT, B_LD = BN * 4 / NT;
+  constexpr int LD = A_LD + B_LD;
+  static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the workgroup");
+  static_assert(WN == 64, "the LDS epilogue assumes 64 output columns per wave");
+  static_assert(NW * WM * WN * 2 <= S * (BM + BN) * 64, "epilogue staging does not fit in the ring");
+  uint4(*As)[BM * 4] = reinterpret_cast<uint4(*)[BM * 4]>(smem);
+  uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BM * 4);
+
+  const int z = blockIdx.z;
+  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa;
+  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb;
+  const int K = g.K;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // loads: pass i covers chunk ids i*NT + tid: row = i*(NT/4) + (tid >> 2), slot = tid & 3.
+  // Address = uniform base of (tile row 0, pass i, stage k0) + per-lane byte offset.
+  // MEDGE (the last tile along M when r != 0): rows past M-1 are fetched from row M-1, so
+  // every load stays in bounds; their products land in rows the epilogue never stores.
+  const int ld_row = tid >> 2;
+  const int ld_c = (tid & 3) ^ ((ld_row >> 2) & 3);
+  uint32_t a_off[A_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    int row = ld_row + i * (NT / 4);
+    if (MEDGE) row = (m0 + row < g.M) ? row : (g.M - 1 - m0);
+    a_off[i] = (uint32_t)(row * g.lda + ld_c * 8) * 2u;
+  }
+  const uint32_t b_off = (uint32_t)(ld_row * g.ldb + ld_c * 8) * 2u;
+  const u16* a_base = A + (long long)m0 * g.lda;
+  const u16* b_base = B + (long long)n0 * g.ldb;
+  const long long b_pass = (long long)(NT / 4) * g.ldb;
+  const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&As[0][wave * 64]));
+  const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&Bs[0][wave * 64]));
+  auto dma = [&](int ks, int slot) {
+    const int k0 = ks << 5;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i)
+      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BM * 64) + i * NT * 16);
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i)
+      dma16_so(b_off, b_base + i * b_pass + k0, b_dst + slot * (BN * 64) + i * NT * 16);
+  };
+
+  // fragment reads: lane -> row (lane & 15), logical chunk (lane >> 4)
+  const int fr_row = lane & 15;
+  const int fr_q = lane >> 4;
+  const int fr_phys = fr_q ^ ((fr_row >> 2) & 3);
+  const int fr_a = (wm * WM + fr_row) * 4 + fr_phys;
+  const int fr_b = (wn * WN + fr_row) * 4 + fr_phys;
+
+  f32x4 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int KS = K >> 5;
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < KS) dma(s, s);
+
+  bf16x8 xa[2][TM], wb[2][TN];
+  if (KS - 1 >= S - 2)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
+  else
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(As[0][fr_a + j * 64]);
+#pragma unroll
+  for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(Bs[0][fr_b + i * 64]);
+
+  for (int base = 0; base < KS; base += S) {
+#pragma unroll
+    for (int u = 0; u < S; ++u) {  // unrolled: ring slot and register set are compile-time
+      const int ks = base + u;
+      if (ks < KS) {
+        const int cur = u & 1;
+        const int slot_next = (u + 1) % S, slot_free = (u + S - 1) % S;
+        if (ks + 1 < KS) {
+          // stage ks+1 may have min(S-3, KS-ks-2) younger stages still in flight behind it
+          if (KS - ks - 2 >= S - 3)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
+          else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+          if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
+#pragma unroll
+          for (int j = 0; j < TM; ++j) xa[cur ^ 1][j] = as_bf16x8(As[slot_next][fr_a + j * 64]);
+#pragma unroll
+          for (int i = 0; i < TN; ++i) wb[cur ^ 1][i] = as_bf16x8(Bs[slot_next][fr_b + i * 64]);
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+          for (int j = 0; j < TM; ++j)
+            acc[i][j] =
+                __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
+  const float alpha = g.alpha;
+  const int epi = g.epilogue;
+  float bias4[TN][4];
+#pragma unroll
+  for (int i = 0; i < TN; ++i) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) bias4[i][v] = 0.f;
+    if (epi != NIMBLE_EPI_NONE) {
+      const uint2 bb = *(const uint2*)((const u16*)g.bias + n0 + wn * WN + i * 16 + fr_q * 4);
+      bias4[i][0] = bf2f((u16)(bb.x & 0xffff));
+      bias4[i][1] = bf2f((u16)(bb.x >> 16));
+      bias4[i][2] = bf2f((u16)(bb.y & 0xffff));
+      bias4[i][3] = bf2f((u16)(bb.y >> 16));
+    }
+  }
+  if (g.out_f32) {
+    float* C = (float*)g.c + (long long)z * g.sc;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int m = m0 + wm * WM + j * 16 + fr_row;
+      if (MEDGE && m >= g.M) continue;
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+        const int n = n0 + wn * WN + i * 16 + fr_q * 4;
+        float4 o;
+        o.x = epilogue(acc[i][j][0], alpha, bias4[i][0], epi);
+        o.y = epilogue(acc[i][j][1], alpha, bias4[i][1], epi);
+        o.z = epilogue(acc[i][j][2], alpha, bias4[i][2], epi);
+        o.w = epilogue(acc[i][j][3], alpha, bias4[i][3], epi);
+        *(float4*)(C + (long long)m * g.ldc + n) = o;
+      }
+    }
+    return;
+  }
+  // bf16: every wave stages its [WM][64] block in LDS (rows of 128 bytes, chunk c of
+  // row r at slot c ^ ((r >> 1) & 7)) and writes it back out as full 128-byte lines
+  __syncthreads();  // all fragment reads of the ring are done
+  unsigned char* region = (unsigned char*)smem + wave * (WM * WN * 2);
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int row = j * 16 + fr_row;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int col = i * 16 + fr_q * 4;
+      const int chunk = (col >> 3) ^ ((row >> 1) & 7);
+      uint2 pk;
+      pk.x = pack_bf16x2(epilogue(acc[i][j][0], alpha, bias4[i][0], epi),
+                         epilogue(acc[i][j][1], alpha, bias4[i][1], epi));
+      pk.y = pack_bf16x2(epilogue(acc[i][j][2], alpha, bias4[i][2], epi),
+                         epilogue(acc[i][j][3], alpha, bias4[i][3], epi));
+      *(uint2*)(region + row * 128 + chunk * 16 + (col & 4) * 2) = pk;
+    }
+  }
+  // the region is private to the wave: no workgroup barrier, the compiler orders the LDS accesses
+  u16* C = (u16*)g.c + (long long)z * g.sc;
+#pragma unroll
+  for (int p = 0; p < WM / 8; ++p) {
+    const int row = p * 8 + (lane >> 3);
+    const int c = lane & 7;
+    const uint4 v = *(const uint4*)(region + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
+    if (MEDGE && m0 + wm * WM + row >= g.M) continue;
+    *(uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + c * 8) = v;
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
+__global__ void __launch_bounds__(WGM* WGN * 64)
+    gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+  __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  if (RESIDUE) {
+    // the packed epilogue needs 16-byte aligned output rows; K must be whole 32-wide stages
+    const bool ragged = (n0 + BN > g.N) || ((g.K & 31) != 0) || ((g.ldc & 7) != 0);
+    if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
+      gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      return;
+    }
+    if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
+      gemm_ring_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      return;
+    }
+  }
+  gemm_ring_body<BM, BN, WGM, WGN, false>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------
@@ -478,6 +764,21 @@ static int launch_tile(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   return check_hip(hipGetLastError(), "tile kernel launch");
 }
 
+template <int BM, int BN, int WGM, int WGN>
+static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  int group_m = 4;
+  if (group_m > tiles_m) group_m = tiles_m;
+  dim3 grid(p.grid[0], 1, p.grid[2]), block(WGM * WGN * 64);
+  if (p.residue_copy)
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
+  else
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
+  return check_hip(hipGetLastError(), "ring kernel launch");
+}
+
 template <bool LSTM>
 static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t st) {
   dim3 grid(p.grid[0], p.grid[1], 1), block(256);
@@ -514,9 +815,9 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
     }
     case NIMBLE_VAR_T32x128: return launch_tile<32, 128, 1, 4>(g, p, st);
     case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
-    case NIMBLE_VAR_T128x128: return launch_tile<128, 128, 2, 2>(g, p, st);
-    case NIMBLE_VAR_T256x128: return launch_tile<256, 128, 2, 2>(g, p, st);
-    case NIMBLE_VAR_T256x256: return launch_tile<256, 256, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T256x128: return launch_ring<256, 128, 4, 2>(g, p, st);
+    case NIMBLE_VAR_T256x256: return launch_ring<256, 256, 2, 4>(g, p, st);
     default: return fail(NIMBLE_ERR_ARG, "unknown variant %d", p.variant);
   }
 }
@@ -540,7 +841,7 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
   if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32)
     return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
   nimble_plan p;
-  int rc = plan_dense(1, M, N, K, force_variant, &p);
+  int rc = plan_dense(1, M, N, K, epilogue, force_variant, &p);
   if (rc != NIMBLE_OK) return rc;
   if (M == 0 || N == 0) return NIMBLE_OK;
   if (!x || !w || !y) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
@@ -565,7 +866,22 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
   g.epilogue = epilogue;
   g.out_f32 = out_dtype == NIMBLE_F32;
   g.batch = 1;
-  return launch_gemm(g, p, (hipStream_t)stream);
+  if (p.split_rows <= 0) return launch_gemm(g, p, (hipStream_t)stream);
+
+  // x = bm*k + r dispatched as two launches: rows [0, bm*k) through the r = 0 copy, then the
+  // r residue rows through the variant the plan chose for them
+  nimble_plan rp;
+  rc = plan_dense(1, M - p.split_rows, N, K, epilogue, p.residue_variant, &rp);
+  if (rc != NIMBLE_OK) return rc;
+  GemmArgs head = g;
+  head.M = (int)p.split_rows;
+  rc = launch_gemm(head, p, (hipStream_t)stream);
+  if (rc != NIMBLE_OK) return rc;
+  GemmArgs tail = g;
+  tail.M = (int)(M - p.split_rows);
+  tail.a = (const u16*)x + p.split_rows * K;
+  tail.c = g.out_f32 ? (void*)((float*)y + p.split_rows * N) : (void*)((u16*)y + p.split_rows * N);
+  return launch_gemm(tail, rp, (hipStream_t)stream);
 }
 
 int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch, int64_t M,
@@ -606,7 +922,7 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
   g.batch = (int)batch;
   // batch slices of a K-contiguous operand stay 16-byte aligned only if M*K (N*K) is a multiple of 8
   if (p.variant != NIMBLE_VAR_GENERIC && (((M * K) & 7) != 0 || ((N * K) & 7) != 0)) {
-    rc = plan_dense(batch, M, N, K, NIMBLE_VAR_GENERIC, &p);
+    rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, &p);
     if (rc != NIMBLE_OK) return rc;
   }
   return launch_gemm(g, p, (hipStream_t)stream);

@@ -120,7 +120,7 @@ def test_plan_residue_identity_for_every_tiled_variant(variant):
             tiles_m = p.k + (1 if p.r else 0)
             assert tiles_m * bm >= M > (tiles_m - 1) * bm
             assert p.grid[0] == tiles_m * -(-N // bn) and p.grid[2] == 1
-            expect_residue = int(p.r != 0 or N % bn != 0 or K % 64 != 0)
+            expect_residue = int(p.r != 0 or N % bn != 0 or K % p.bk != 0)
             assert p.residue_copy == expect_residue
             assert p.workspace_bytes == 0
 
@@ -134,12 +134,33 @@ def test_auto_dispatch_table():
     assert nb.dense_plan(65, 2048, 1024).name.startswith("t")
     assert nb.dense_plan(8192, 4096, 1024).name in ("t256x256", "t256x128")
     assert nb.dense_plan(8192, 4096, 1024).residue_copy == 0
-    assert nb.dense_plan(8193, 4096, 1024).residue_copy == 1
+    # one row past a tile boundary: either the r != 0 copy, or the split dispatch
+    # (k full tiles through the r = 0 copy, the residue rows through a small-M kernel)
+    p = nb.dense_plan(8193, 4096, 1024)
+    assert p.k * p.bm + p.r == 8193 and p.r == 1
+    if p.split_rows:
+        assert p.split_rows == p.k * p.bm and p.residue_copy == 0
+        assert nb.variant_name(p.residue_variant) == "skinny16"
+        assert p.grid[0] == (p.split_rows // p.bm) * (4096 // p.bn)
+    else:
+        assert p.residue_copy == 1
     assert nb.dense_plan(100, 128, 100).name == "generic"
     assert nb.dense_plan(100, 128, 0).name == "generic"
     for M in range(65, 1200, 7):
         p = nb.dense_plan(M, 3072, 768)
         assert p.k * p.bm + p.r == M
+    for M in range(2048, 2048 + 600, 5):
+        for (N, K) in ((4096, 1024), (1024, 4096)):
+            p = nb.dense_plan(M, N, K)
+            assert p.k * p.bm + p.r == M and 0 <= p.r < p.bm
+            if p.split_rows:
+                assert p.split_rows == p.k * p.bm and 0 < M - p.split_rows == p.r
+                assert p.residue_copy == 0 and N % p.bn == 0 and K % p.bk == 0
+                assert nb.variant_name(p.residue_variant) is not None
+                if p.r <= 64:
+                    assert nb.variant_name(p.residue_variant) == "skinny16"
+            forced = nb.dense_plan(M, N, K, force_variant=p.variant)
+            assert forced.split_rows == 0  # a forced variant is one launch
 
 
 def test_plan_rejects_bad_arguments():
