@@ -102,7 +102,7 @@ def bench_config5(steps: int, warmup: int):
     roofline = {
         "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": _traffic_note(),
-        "kernel": "gemm_tile_kernel (" + ",".join(plans) + ")", "launches": launches,
+        "kernel": "gemm_ring_kernel (" + ",".join(plans) + ")", "launches": launches,
         "avg_launch_us": round(k_ms * 1e3 / launches, 2),
         "flops_per_launch": round(k_flops / launches),
     }
@@ -206,6 +206,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 512 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
@@ -221,6 +223,13 @@ def main():
     nb.load()
     torch.cuda.set_device(0)
 
+    if args.copy_probe:
+        src = torch.empty(512 * 1024 * 1024, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     res = bench_config5(args.steps, args.warmup)
     line = {
         "metric": "dynamic-M dense TFLOP/s (bf16) over M sweep; % of MFMA/HBM roofline",

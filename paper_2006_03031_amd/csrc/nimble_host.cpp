@@ -98,7 +98,12 @@ static const double kLaunchGapUs = 4.0;
 static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue) {
   const VariantInfo& vi = kVariants[v];
   const int64_t tiles = batch * ceil_div(rows, vi.bm) * ceil_div(N, vi.bn);
-  const double t_full = tile_cost(v, K, epilogue) * kUsPerUnit;
+  // one K step of a tile cannot go faster than the latency of its loads: about 1.8 us per
+  // 64-wide step in the register-staged small-tile kernels, 0.3 us per 32-wide ring stage
+  const double latency_floor = (v <= NIMBLE_VAR_T64x128) ? (double)ceil_div(K, 64) * 1.8
+                                                         : (double)ceil_div(K, 32) * 0.3;
+  double t_full = tile_cost(v, K, epilogue) * kUsPerUnit;
+  if (t_full < latency_floor) t_full = latency_floor;
   const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
   double us = (double)full_rounds * t_full;
   if (rem > 0) {

@@ -339,7 +339,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, bool MEDGE>
+template <int BM, int BN, int WGM, int WGN, bool MEDGE, bool PINGPONG>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
                                                uint4* smem) {
   constexpr int S = 4;
@@ -409,43 +409,100 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   for (int s = 0; s < S - 1; ++s)
     if (s < KS) dma(s, s);
 
-  bf16x8 xa[2][TM], wb[2][TN];
   if (KS - 1 >= S - 2)
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
   else
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-#pragma unroll
-  for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(As[0][fr_a + j * 64]);
-#pragma unroll
-  for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(Bs[0][fr_b + i * 64]);
 
-  for (int base = 0; base < KS; base += S) {
+  if constexpr (PINGPONG) {
+    // Waves w and w + NW/2 share a SIMD.  The workgroup runs in two groups half a step out of
+    // phase: while group P multiplies stage s, group Q issues its loads and reads its fragments
+    // of stage s, then they swap.  A wave never has memory instructions and MFMAs queued
+    // together, and the matrix core of each SIMD always has one wave feeding it.
+    //   P:    mem(0) | mfma(0) | mem(1) | mfma(1) | ...        ("|" = workgroup barrier)
+    //   Q:  |        | mem(0)  | mfma(0)| mem(1)  | ...
+    // mem(s) refills the slot of stage s-1 (both groups finished reading it before the barrier
+    // that starts the phase) with stage s+3, then reads the fragments of stage s.  Before the
+    // barrier that precedes P's mem(s+1) every wave has waited for its own loads of stage s+1.
+    const bool is_q = wave >= NW / 2;
+    bf16x8 xa[TM], wb[TN];
+    if (is_q) __syncthreads();
+    for (int base = 0; base < KS; base += S) {
 #pragma unroll
-    for (int u = 0; u < S; ++u) {  // unrolled: ring slot and register set are compile-time
-      const int ks = base + u;
-      if (ks < KS) {
-        const int cur = u & 1;
-        const int slot_next = (u + 1) % S, slot_free = (u + S - 1) % S;
-        if (ks + 1 < KS) {
-          // stage ks+1 may have min(S-3, KS-ks-2) younger stages still in flight behind it
-          if (KS - ks - 2 >= S - 3)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
-          else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-          __syncthreads();
+      for (int u = 0; u < S; ++u) {
+        const int ks = base + u;
+        if (ks < KS) {
+          const int slot = u % S, slot_free = (u + S - 1) % S;
           if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
 #pragma unroll
-          for (int j = 0; j < TM; ++j) xa[cur ^ 1][j] = as_bf16x8(As[slot_next][fr_a + j * 64]);
+          for (int j = 0; j < TM; ++j) xa[j] = as_bf16x8(As[slot][fr_a + j * 64]);
 #pragma unroll
-          for (int i = 0; i < TN; ++i) wb[cur ^ 1][i] = as_bf16x8(Bs[slot_next][fr_b + i * 64]);
+          for (int i = 0; i < TN; ++i) wb[i] = as_bf16x8(Bs[slot][fr_b + i * 64]);
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          if (is_q && ks + 1 < KS) {
+            if (ks + S - 1 < KS)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_s_setprio(0);
+          if (!is_q && ks + 1 < KS) {
+            if (ks + S - 1 < KS)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
         }
+      }
+    }
+    if (!is_q) __syncthreads();
+  } else {
+    bf16x8 xa[2][TM], wb[2][TN];
 #pragma unroll
-        for (int i = 0; i < TN; ++i)
+    for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(As[0][fr_a + j * 64]);
 #pragma unroll
-          for (int j = 0; j < TM; ++j)
-            acc[i][j] =
-                __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(Bs[0][fr_b + i * 64]);
+
+    for (int base = 0; base < KS; base += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u) {  // unrolled: ring slot and register set are compile-time
+        const int ks = base + u;
+        if (ks < KS) {
+          const int cur = u & 1;
+          const int slot_next = (u + 1) % S, slot_free = (u + S - 1) % S;
+          if (ks + 1 < KS) {
+            // stage ks+1 may have min(S-3, KS-ks-2) younger stages still in flight behind it
+            if (KS - ks - 2 >= S - 3)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) xa[cur ^ 1][j] = as_bf16x8(As[slot_next][fr_a + j * 64]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) wb[cur ^ 1][i] = as_bf16x8(Bs[slot_next][fr_b + i * 64]);
+          }
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+              acc[i][j] =
+                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
+        }
       }
     }
   }
@@ -519,6 +576,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
 __global__ void __launch_bounds__(WGM* WGN * 64)
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+  // the two-group schedule pays off when a wave's multiply phase is long: 128x64 wave tiles
+  constexpr bool kPingPong = (BM / WGM) * (BN / WGN) >= 128 * 64 && WGM * WGN == 8;
   __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
@@ -531,11 +590,11 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
       return;
     }
     if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
-      gemm_ring_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      gemm_ring_body<BM, BN, WGM, WGN, true, kPingPong>(g, m0, n0, smem);
       return;
     }
   }
-  gemm_ring_body<BM, BN, WGM, WGN, false>(g, m0, n0, smem);
+  gemm_ring_body<BM, BN, WGM, WGN, false, kPingPong>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------
