@@ -32,14 +32,16 @@ def _to_dev(arr):
 
 
 def _traffic_note():
-    """HBM bytes per dense launch measured with rocprofv3 --pmc (FETCH_SIZE and
-    WRITE_SIZE, scaled by a copy kernel of known size); recorded under profiles/."""
-    path = os.path.join(ROOT, "profiles", "dense_config5_traffic.json")
-    if os.path.exists(path):
-        try:
-            return json.load(open(path)).get("hbm_bytes_per_launch")
-        except Exception:
-            return None
+    """HBM-side bytes per dense launch from two rocprofv3 --pmc runs (FETCH_SIZE, then
+    WRITE_SIZE, each scaled by a plain copy of known size); the summary of those runs is
+    profiles/dense_config5_hbm_traffic.txt, which carries the figure on one line."""
+    path = os.path.join(ROOT, "profiles", "dense_config5_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("hbm_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
     return None
 
 
