@@ -64,9 +64,10 @@ typedef enum nimble_dtype { NIMBLE_BF16 = 0, NIMBLE_F32 = 1 } nimble_dtype;
 /* The kernel family the dispatch function chooses from.  Every tiled variant
  * exists in two copies: one compiled for residue r = 0 (no bounds code at
  * all) and one for r != 0 (the last tile along M is clamped and masked).  When
- * r is small against the tile the dispatch function may instead split the call:
- * the k full tiles go to the r = 0 copy and the r residue rows to a variant
- * built for few rows (see nimble_plan.split_rows). */
+ * it pays, the dispatch function instead splits the call in two launches: whole
+ * tile rows (all k of them, or as many as fill whole rounds of the chip) go to
+ * the r = 0 copy, and the remaining rows, residue included, to the variant that
+ * suits their number (see nimble_plan.split_rows). */
 typedef enum nimble_variant {
   NIMBLE_VAR_AUTO = -1,
   NIMBLE_VAR_GENERIC = 0,    /* any M,N,K; fully bounds checked, scalar FMA       */
@@ -90,9 +91,9 @@ typedef struct nimble_plan {
   uint32_t grid[3];       /* launch grid                                          */
   uint32_t block;         /* threads per workgroup                                */
   uint64_t workspace_bytes; /* device scratch the launch needs                    */
-  int64_t split_rows;     /* > 0: two launches.  Rows [0, split_rows) = k*bm run the   */
-                          /* r = 0 copy of `variant`; the r residue rows run           */
-  int32_t residue_variant;/* this variant, a kernel specialised for few rows           */
+  int64_t split_rows;     /* > 0: two launches.  Rows [0, split_rows), a whole number  */
+                          /* of tiles (at most k*bm), run the r = 0 copy of `variant`; */
+  int32_t residue_variant;/* the remaining rows run this variant in a second launch    */
   int32_t reserved;
 } nimble_plan;
 

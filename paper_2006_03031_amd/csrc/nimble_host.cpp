@@ -49,8 +49,8 @@ static double tile_cost(int variant, int64_t K, int epilogue) {
   switch (variant) {
     case NIMBLE_VAR_T32x128: eff = 0.30; break;
     case NIMBLE_VAR_T64x128: eff = 0.50; break;
-    case NIMBLE_VAR_T128x128: eff = 0.87; break;
-    case NIMBLE_VAR_T256x128: eff = 0.97; break;
+    case NIMBLE_VAR_T128x128: eff = 0.80; break;
+    case NIMBLE_VAR_T256x128: eff = 0.87; break;
     case NIMBLE_VAR_T256x256: eff = 1.00; break;
     default: return 1e30;
   }
@@ -83,8 +83,9 @@ static void fill_tiled(nimble_plan* p, int variant, int64_t batch, int64_t M, in
   p->workspace_bytes = 0;
 }
 
-// One unit of tile_cost in microseconds (a 256x256 tile at K = 1024 with GELU takes about 42 us).
-static const double kUsPerUnit = 5.1e-7;
+// One unit of tile_cost in microseconds (a 256x256 tile at K = 1024 with GELU takes about 37 us
+// when the whole chip is busy).
+static const double kUsPerUnit = 4.4e-7;
 // Gap between two dependent launches on one stream, microseconds.
 static const double kLaunchGapUs = 4.0;
 
@@ -177,17 +178,28 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
         double best_us = single_us;
         for (int v = NIMBLE_VAR_T128x128; v <= NIMBLE_VAR_T256x256; ++v) {
           const VariantInfo& vi = kVariants[v];
-          const int64_t k = M / vi.bm, r = M % vi.bm;
-          if (k == 0 || r == 0 || N % vi.bn != 0 || K % vi.bk != 0) continue;
-          double res_us = 0;
-          const int rv = best_for_residue(r, N, K, epilogue, &res_us);
-          if (rv < 0) continue;
-          const double us = tiled_cost_us(v, 1, k * vi.bm, N, K, epilogue) + kLaunchGapUs + res_us;
-          if (us < best_us) {
-            best_us = us;
-            variant = v;
-            split_rows = k * vi.bm;
-            residue_variant = rv;
+          if (N % vi.bn != 0 || K % vi.bk != 0) continue;
+          // candidate cut points: all k full tile rows, or only as many tile rows as fill
+          // whole rounds of the chip (then the second launch takes a larger remainder)
+          const int64_t tiles_n = N / vi.bn;
+          int64_t cuts[2] = {(M / vi.bm) * vi.bm, 0};
+          if (kCUs % tiles_n == 0) {
+            const int64_t rows_per_round = (kCUs / tiles_n) * vi.bm;
+            cuts[1] = (M / rows_per_round) * rows_per_round;
+          }
+          for (int c = 0; c < 2; ++c) {
+            const int64_t head = cuts[c], rest = M - head;
+            if (head <= 0 || rest <= 0 || (c == 1 && head == cuts[0])) continue;
+            double res_us = 0;
+            const int rv = best_for_residue(rest, N, K, epilogue, &res_us);
+            if (rv < 0) continue;
+            const double us = tiled_cost_us(v, 1, head, N, K, epilogue) + kLaunchGapUs + res_us;
+            if (us < best_us) {
+              best_us = us;
+              variant = v;
+              split_rows = head;
+              residue_variant = rv;
+            }
           }
         }
       }

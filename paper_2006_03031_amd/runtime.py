@@ -22,6 +22,33 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+class StorageArena:
+    """One backing storage allocated up front, tensors carved out of it at offsets computed
+    from the shape function's result: alloc_storage once, then alloc_tensor(storage, offset,
+    shape, dtype) per operator (Section 3.3, storage coalescing).  `reset()` rewinds the
+    offset; the caller does that once per inference when the previous outputs are dead."""
+
+    def __init__(self, capacity_bytes: int, device="cuda"):
+        self.alignment = max(256, nb.storage_alignment())
+        self.storage = torch.empty(int(capacity_bytes) + self.alignment, dtype=torch.uint8, device=device)
+        base = self.storage.data_ptr()
+        self._base_off = (-base) % self.alignment
+        self.capacity = int(capacity_bytes)
+        self.offset = 0
+
+    def reset(self) -> None:
+        self.offset = 0
+
+    def alloc(self, shape, dtype: int) -> torch.Tensor:
+        nbytes = nb.storage_bytes(shape, dtype)
+        start = (self.offset + self.alignment - 1) // self.alignment * self.alignment
+        if start + nbytes > self.capacity:
+            raise MemoryError(f"arena of {self.capacity} bytes cannot hold {nbytes} more at offset {start}")
+        self.offset = start + nbytes
+        flat = self.storage[self._base_off + start:self._base_off + start + nbytes]
+        return flat.view(_TORCH_DTYPE[dtype]).view(tuple(shape))
+
+
 def _alloc(shape, dtype: int, device) -> torch.Tensor:
     # alloc_storage(size, alignment, device) + alloc_tensor(storage, 0, shape, dtype):
     # torch's caching allocator returns storage aligned to at least 512 bytes.
@@ -31,10 +58,15 @@ def _alloc(shape, dtype: int, device) -> torch.Tensor:
 
 def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilogue: int = nb.EPI_BIAS,
           out_dtype: int = nb.BF16, force_variant: int = nb.VAR_AUTO,
-          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+          out: Optional[torch.Tensor] = None, arena: Optional[StorageArena] = None) -> torch.Tensor:
     M, N = nb.nimble_dense_shape(tuple(x.shape), tuple(w.shape))
     K = x.shape[1]
-    y = out if out is not None else _alloc((M, N), out_dtype, x.device)
+    if out is not None:
+        y = out
+    elif arena is not None:
+        y = arena.alloc((M, N), out_dtype)
+    else:
+        y = _alloc((M, N), out_dtype, x.device)
     nb.nimble_dense_dyn(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else 0,
                         y.data_ptr(), M, N, K, epilogue, out_dtype, force_variant, 0, 0, _stream())
     return y

@@ -149,15 +149,17 @@ def test_auto_dispatch_table():
     for M in range(65, 1200, 7):
         p = nb.dense_plan(M, 3072, 768)
         assert p.k * p.bm + p.r == M
-    for M in range(2048, 2048 + 600, 5):
+    for M in list(range(2048, 2048 + 600, 5)) + list(range(5700, 10700, 37)):
         for (N, K) in ((4096, 1024), (1024, 4096)):
             p = nb.dense_plan(M, N, K)
             assert p.k * p.bm + p.r == M and 0 <= p.r < p.bm
             if p.split_rows:
-                assert p.split_rows == p.k * p.bm and 0 < M - p.split_rows == p.r
+                assert p.split_rows % p.bm == 0 and 0 < p.split_rows <= p.k * p.bm
+                assert M - p.split_rows >= p.r and M - p.split_rows > 0
                 assert p.residue_copy == 0 and N % p.bn == 0 and K % p.bk == 0
+                assert p.grid[0] == (p.split_rows // p.bm) * (N // p.bn)
                 assert nb.variant_name(p.residue_variant) is not None
-                if p.r <= 64:
+                if M - p.split_rows <= 64:
                     assert nb.variant_name(p.residue_variant) == "skinny16"
             forced = nb.dense_plan(M, N, K, force_variant=p.variant)
             assert forced.split_rows == 0  # a forced variant is one launch
