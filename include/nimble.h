@@ -80,6 +80,10 @@ typedef enum nimble_variant {
   NIMBLE_VAR_COUNT = 7
 } nimble_variant;
 
+/* A forced variant may also force the K split: force_variant = variant | NIMBLE_FORCE_SPLIT_K(n)
+ * cuts K into n slices (ring variants only; needs n*M*N*4 bytes of workspace). */
+#define NIMBLE_FORCE_SPLIT_K(n) (((n) & 0xff) << 8)
+
 /* What the dispatch function decided for one run-time shape (host only). */
 typedef struct nimble_plan {
   int32_t variant;        /* nimble_variant                                       */
@@ -87,7 +91,9 @@ typedef struct nimble_plan {
   int64_t k;              /* floor(M / bm): number of full tiles along M          */
   int32_t r;              /* M mod bm: the residue the kernel copy is chosen by   */
   int32_t residue_copy;   /* 1 when the r != 0 copy (or an N/K edge) is launched  */
-  int32_t split_k;        /* K is cut into this many slices (1 = none)            */
+  int32_t split_k;        /* K is cut into this many slices (1 = none); with > 1  */
+                          /* the slices write f32 partial sums to the workspace   */
+                          /* and a second kernel adds them and applies the epilogue */
   uint32_t grid[3];       /* launch grid                                          */
   uint32_t block;         /* threads per workgroup                                */
   uint64_t workspace_bytes; /* device scratch the launch needs                    */

@@ -66,44 +66,30 @@ bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K) {
   return K > 0 && K % 8 == 0 && K <= (1ll << 22);
 }
 
-static void fill_tiled(nimble_plan* p, int variant, int64_t batch, int64_t M, int64_t N, int64_t K) {
-  const VariantInfo& v = kVariants[variant];
-  p->variant = variant;
-  p->bm = v.bm;
-  p->bn = v.bn;
-  p->bk = v.bk;
-  p->k = M / v.bm;
-  p->r = (int32_t)(M % v.bm);
-  p->residue_copy = (p->r != 0 || N % v.bn != 0 || K % v.bk != 0) ? 1 : 0;
-  p->split_k = 1;
-  p->grid[0] = (uint32_t)(ceil_div(M, v.bm) * ceil_div(N, v.bn));
-  p->grid[1] = 1;
-  p->grid[2] = (uint32_t)batch;
-  p->block = (uint32_t)v.threads;
-  p->workspace_bytes = 0;
-}
-
 // One unit of tile_cost in microseconds (a 256x256 tile at K = 1024 with GELU takes about 37 us
 // when the whole chip is busy).
 static const double kUsPerUnit = 4.4e-7;
 // Gap between two dependent launches on one stream, microseconds.
 static const double kLaunchGapUs = 4.0;
 
-// Estimated time of one launch of tiled variant v over `rows` rows, microseconds.  The
-// tiles run in rounds of one per compute unit.  A full round runs at the chip's
-// power-limited rate; the last, partial round runs faster per tile the fewer units it
-// occupies (measured: about 0.62 of the full-round time when a handful of units are
-// busy, 0.72 at half the chip).  So a dynamic M just past a tile boundary costs most of
+// Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
+// slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
+// at the chip's power-limited rate; the last, partial round runs faster per tile the fewer
+// units it occupies (measured: about 0.62 of the full-round time when a handful of units
+// are busy, 0.72 at half the chip).  So a dynamic M just past a tile boundary costs most of
 // an extra round with big tiles, while smaller tiles quantise more finely but run the
-// matrix cores less efficiently.
-static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue) {
+// matrix cores less efficiently.  Cutting K multiplies the tiles and shortens each; the
+// partial sums then cross HBM once more and a second small kernel adds them up.
+static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
+                            int sk = 1) {
   const VariantInfo& vi = kVariants[v];
-  const int64_t tiles = batch * ceil_div(rows, vi.bm) * ceil_div(N, vi.bn);
+  const int64_t tiles = batch * ceil_div(rows, vi.bm) * ceil_div(N, vi.bn) * sk;
+  const int64_t k_slice = ceil_div(ceil_div(K, 32), sk) * 32;
   // one K step of a tile cannot go faster than the latency of its loads: about 1.8 us per
   // 64-wide step in the register-staged small-tile kernels, 0.3 us per 32-wide ring stage
-  const double latency_floor = (v <= NIMBLE_VAR_T64x128) ? (double)ceil_div(K, 64) * 1.8
-                                                         : (double)ceil_div(K, 32) * 0.3;
-  double t_full = tile_cost(v, K, epilogue) * kUsPerUnit;
+  const double latency_floor = (v <= NIMBLE_VAR_T64x128) ? (double)ceil_div(k_slice, 64) * 1.8
+                                                         : (double)ceil_div(k_slice, 32) * 0.3;
+  double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue) * kUsPerUnit;
   if (t_full < latency_floor) t_full = latency_floor;
   const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
   double us = (double)full_rounds * t_full;
@@ -111,6 +97,7 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
     const double occ = (double)rem / (double)kCUs;
     us += t_full * (0.62 + 0.38 * occ * occ);
   }
+  if (sk > 1) us += kLaunchGapUs + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.0e6;
   return us;
 }
 
@@ -119,34 +106,69 @@ static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
   return 6.0 + (double)ceil_div(rows, 64) * (double)N * (double)K * 2.0 / 3.0e6;
 }
 
-static int best_tiled(int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue, double* cost_us) {
-  int best = -1;
-  double best_cost = 0;
+static bool split_k_ok(int v, int64_t batch, int64_t N, int64_t K, int sk) {
+  if (sk == 1) return true;
+  if (v < NIMBLE_VAR_T128x128 || batch != 1) return false;        // ring kernels, dense only
+  if (N % kVariants[v].bn != 0 || K % 32 != 0) return false;       // no ragged N/K tiles
+  const int64_t stages = K / 32, per = ceil_div(stages, sk);
+  return per >= 4 && per * (sk - 1) < stages;                      // every slice gets work
+}
+
+struct Launch {
+  int variant = -1;
+  int split_k = 1;
+  double us = 0;
+};
+
+// Best single launch for `rows` rows: weight streaming up to 64 rows, else the tiled
+// variant and K split with the least estimated time that fits the workspace.
+static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
+                          uint64_t max_workspace, bool allow_skinny) {
+  Launch best;
+  if (allow_skinny && rows <= 64 && batch == 1) {
+    best.variant = NIMBLE_VAR_SKINNY16;
+    best.us = skinny_cost_us(rows, N, K);
+    return best;
+  }
   for (int v = NIMBLE_VAR_T32x128; v <= NIMBLE_VAR_T256x256; ++v) {
     if (!tiled_variant_ok(v, rows, N, K)) continue;
     if (v > NIMBLE_VAR_T32x128 && rows <= kVariants[v - 1].bm) break;  // tile taller than needed
-    const double cost = tiled_cost_us(v, batch, rows, N, K, epilogue);
-    if (best < 0 || cost < best_cost) {
-      best = v;
-      best_cost = cost;
+    for (int sk = 1; sk <= 16; sk *= 2) {
+      if (!split_k_ok(v, batch, N, K, sk)) continue;
+      if (sk > 1 && (uint64_t)sk * (uint64_t)rows * (uint64_t)N * 4u > max_workspace) continue;
+      const double us = tiled_cost_us(v, batch, rows, N, K, epilogue, sk);
+      if (best.variant < 0 || us < best.us) {
+        best.variant = v;
+        best.split_k = sk;
+        best.us = us;
+      }
     }
   }
-  if (cost_us) *cost_us = best_cost;
   return best;
 }
 
-// Best kernel for a few residue rows: the weight-streaming kernel up to 64 rows, else a small tile.
-static int best_for_residue(int64_t rows, int64_t N, int64_t K, int epilogue, double* cost_us) {
-  if (rows <= 64) {
-    *cost_us = skinny_cost_us(rows, N, K);
-    return NIMBLE_VAR_SKINNY16;
-  }
-  return best_tiled(1, rows, N, K, epilogue, cost_us);
+static void fill_tiled(nimble_plan* p, int variant, int split_k, int64_t batch, int64_t M, int64_t N,
+                       int64_t K) {
+  const VariantInfo& v = kVariants[variant];
+  p->variant = variant;
+  p->bm = v.bm;
+  p->bn = v.bn;
+  p->bk = v.bk;
+  p->k = M / v.bm;
+  p->r = (int32_t)(M % v.bm);
+  p->residue_copy = (p->r != 0 || N % v.bn != 0 || K % v.bk != 0) ? 1 : 0;
+  p->split_k = split_k;
+  p->grid[0] = (uint32_t)(ceil_div(M, v.bm) * ceil_div(N, v.bn));
+  p->grid[1] = (uint32_t)split_k;
+  p->grid[2] = (uint32_t)batch;
+  p->block = (uint32_t)v.threads;
+  p->workspace_bytes = split_k > 1 ? (uint64_t)split_k * (uint64_t)M * (uint64_t)N * 4u : 0;
 }
 
 int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int force_variant,
-               nimble_plan* p) {
+               const PlanOptions& opt, nimble_plan* p) {
   std::memset(p, 0, sizeof(*p));
+  p->residue_variant = NIMBLE_VAR_AUTO;
   if (M < 0 || N < 0 || K < 0 || batch < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (M > (1ll << 30) || N > (1ll << 30) || K > (1ll << 30) || batch > 65535)
     return fail(NIMBLE_ERR_ARG, "extent too large");
@@ -156,31 +178,35 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     const char* env = std::getenv("NIMBLE_FORCE_VARIANT");
     if (env && *env) variant = std::atoi(env);
   }
+  // a forced variant may carry a forced K split in bits 8..15 (NIMBLE_FORCE_SPLIT_K)
+  int forced_sk = opt.force_split_k;
+  if (variant >= 0) {
+    if ((variant >> 8) & 0xff) forced_sk = (variant >> 8) & 0xff;
+    variant &= 0xff;
+  }
   if (variant < NIMBLE_VAR_AUTO || variant >= NIMBLE_VAR_COUNT)
     return fail(NIMBLE_ERR_ARG, "unknown variant %d", variant);
 
   const bool aligned_k = (K > 0 && K % 8 == 0);
   int64_t split_rows = 0;
   int residue_variant = NIMBLE_VAR_AUTO;
+  int split_k = 1;
   if (variant == NIMBLE_VAR_AUTO) {
     if (!aligned_k || M == 0 || N == 0) {
       variant = NIMBLE_VAR_GENERIC;
-    } else if (M <= 64 && batch == 1) {
-      variant = NIMBLE_VAR_SKINNY16;
     } else {
-      double single_us = 0;
-      variant = best_tiled(batch, M, N, K, epilogue, &single_us);
-      if (variant < 0) variant = NIMBLE_VAR_GENERIC;
-      // Alternative: x = bm*k + r as two launches.  The k full tiles run the r = 0 copy of a
-      // big-tile variant (no bounds code, whole rounds of tiles), the r residue rows run a
-      // kernel built for few rows.  Taken when the estimate beats the best single launch.
-      if (variant != NIMBLE_VAR_GENERIC && batch == 1) {
-        double best_us = single_us;
+      const Launch single = best_launch(batch, M, N, K, epilogue, opt.max_workspace, true);
+      variant = single.variant < 0 ? NIMBLE_VAR_GENERIC : single.variant;
+      split_k = single.split_k;
+      // Alternative: two launches.  Whole tile rows (all k of them, or as many as fill whole
+      // rounds of the chip) run the r = 0 copy of a big-tile variant: no bounds code, no
+      // partial round.  The remaining rows, residue included, run whatever suits their
+      // number.  Taken when the estimate beats the best single launch.
+      if (opt.allow_row_split && variant >= NIMBLE_VAR_T32x128 && batch == 1) {
+        double best_us = single.us;
         for (int v = NIMBLE_VAR_T128x128; v <= NIMBLE_VAR_T256x256; ++v) {
           const VariantInfo& vi = kVariants[v];
           if (N % vi.bn != 0 || K % vi.bk != 0) continue;
-          // candidate cut points: all k full tile rows, or only as many tile rows as fill
-          // whole rounds of the chip (then the second launch takes a larger remainder)
           const int64_t tiles_n = N / vi.bn;
           int64_t cuts[2] = {(M / vi.bm) * vi.bm, 0};
           if (kCUs % tiles_n == 0) {
@@ -190,15 +216,15 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
           for (int c = 0; c < 2; ++c) {
             const int64_t head = cuts[c], rest = M - head;
             if (head <= 0 || rest <= 0 || (c == 1 && head == cuts[0])) continue;
-            double res_us = 0;
-            const int rv = best_for_residue(rest, N, K, epilogue, &res_us);
-            if (rv < 0) continue;
-            const double us = tiled_cost_us(v, 1, head, N, K, epilogue) + kLaunchGapUs + res_us;
+            const Launch tail = best_launch(1, rest, N, K, epilogue, opt.max_workspace, true);
+            if (tail.variant < 0) continue;
+            const double us = tiled_cost_us(v, 1, head, N, K, epilogue) + kLaunchGapUs + tail.us;
             if (us < best_us) {
               best_us = us;
               variant = v;
+              split_k = 1;
               split_rows = head;
-              residue_variant = rv;
+              residue_variant = tail.variant;
             }
           }
         }
@@ -242,15 +268,22 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
   }
   if (!tiled_variant_ok(variant, M, N, K))
     return fail(NIMBLE_ERR_ARG, "variant %s cannot run K=%lld", kVariants[variant].name, (long long)K);
-  fill_tiled(p, variant, batch, split_rows > 0 ? split_rows : M, N, K);
+  if (force_variant != NIMBLE_VAR_AUTO && forced_sk > 0) {
+    if (!split_k_ok(variant, batch, N, K, forced_sk))
+      return fail(NIMBLE_ERR_ARG, "variant %s cannot cut K=%lld into %d slices", kVariants[variant].name,
+                  (long long)K, forced_sk);
+    if (forced_sk > 1 && (uint64_t)forced_sk * (uint64_t)M * (uint64_t)N * 4u > opt.max_workspace)
+      return fail(NIMBLE_ERR_WORKSPACE, "cutting K into %d slices needs %llu bytes of workspace", forced_sk,
+                  (unsigned long long)((uint64_t)forced_sk * (uint64_t)M * (uint64_t)N * 4u));
+    split_k = forced_sk;
+  }
+  fill_tiled(p, variant, split_k, batch, split_rows > 0 ? split_rows : M, N, K);
   if (split_rows > 0) {
     // k and r describe the whole call; grid and residue_copy describe the first launch
     p->k = M / p->bm;
     p->r = (int32_t)(M % p->bm);
     p->split_rows = split_rows;
     p->residue_variant = residue_variant;
-  } else {
-    p->residue_variant = NIMBLE_VAR_AUTO;
   }
   return NIMBLE_OK;
 }
@@ -357,7 +390,9 @@ int nimble_dense_plan(int64_t M, int64_t N, int64_t K, int epilogue, int out_dty
   if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
     return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
   if (dtype_size(out_dtype) == 0) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
-  return plan_dense(1, M, N, K, epilogue, force_variant, plan);
+  PlanOptions opt;
+  opt.max_workspace = ~0ull;  // report the plan for a caller that provides what it asks for
+  return plan_dense(1, M, N, K, epilogue, force_variant, opt, plan);
 }
 
 int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b,
@@ -367,9 +402,9 @@ int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int
   if (dtype_size(out_dtype) == 0) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
   if (!trans_b) {
     // b is (T,K,N): rows of b are not K-contiguous; the bounds-checked kernel reads it strided
-    return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, plan);
+    return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), plan);
   }
-  return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, plan);
+  return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, PlanOptions(), plan);
 }
 
 int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {

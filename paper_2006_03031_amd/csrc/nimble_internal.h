@@ -18,9 +18,15 @@ void clear_error();
 
 bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
 
+struct PlanOptions {
+  uint64_t max_workspace = 0;   // bytes of caller scratch available (split-K partial sums)
+  bool allow_row_split = true;  // may dispatch x = bm*k + r as two launches
+  int force_split_k = 0;        // > 0 with a forced variant: cut K into exactly this many slices
+};
+
 // Dispatch table shared by dense (batch = 1) and batch_matmul.
 int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int force_variant,
-               nimble_plan* p);
+               const PlanOptions& opt, nimble_plan* p);
 
 // One C = epi(alpha * A.B^T + bias) problem as the kernels see it.  A is
 // [M,K] with row stride lda, B is [N,K] with row stride ldb (or, when

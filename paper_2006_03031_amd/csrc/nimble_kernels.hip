@@ -355,10 +355,15 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   uint4(*As)[BM * 4] = reinterpret_cast<uint4(*)[BM * 4]>(smem);
   uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BM * 4);
 
+  // gridDim.y > 1: K is cut into gridDim.y slices of whole stages; slice blockIdx.y writes its
+  // f32 partial sums to its own [M,N] plane of the output (g.c is then the split-K workspace)
   const int z = blockIdx.z;
-  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa;
-  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb;
-  const int K = g.K;
+  const int stages_all = g.K >> 5;
+  const int stages_per = (stages_all + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int stage0 = (int)blockIdx.y * stages_per;
+  const int KS = (stages_all - stage0) < stages_per ? (stages_all - stage0) : stages_per;
+  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa + (stage0 << 5);
+  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb + (stage0 << 5);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
@@ -404,7 +409,6 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 #pragma unroll
     for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int KS = K >> 5;
 #pragma unroll
   for (int s = 0; s < S - 1; ++s)
     if (s < KS) dma(s, s);
@@ -524,7 +528,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     }
   }
   if (g.out_f32) {
-    float* C = (float*)g.c + (long long)z * g.sc;
+    float* C = (float*)g.c + (long long)z * g.sc + (long long)blockIdx.y * g.M * g.ldc;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
       const int m = m0 + wm * WM + j * 16 + fr_row;
@@ -801,6 +805,43 @@ __global__ void __launch_bounds__(256)
 }
 
 // ---------------------------------------------------------------------------
+// Second half of a K-split launch: add the `slices` f32 partial planes, apply the epilogue,
+// write the output.  One thread per 4 consecutive columns (N is a multiple of 128 here).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+    splitk_reduce_kernel(const float* __restrict__ ws, int slices, long long plane, int M, int N,
+                         const u16* __restrict__ bias, int epi, void* __restrict__ out, int out_f32) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= (long long)M * N) return;
+  float4 acc = *(const float4*)(ws + idx);
+  for (int s = 1; s < slices; ++s) {
+    const float4 v = *(const float4*)(ws + (long long)s * plane + idx);
+    acc.x += v.x;
+    acc.y += v.y;
+    acc.z += v.z;
+    acc.w += v.w;
+  }
+  float b4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (epi != NIMBLE_EPI_NONE) {
+    const uint2 bb = *(const uint2*)(bias + (int)(idx % N));
+    b4[0] = bf2f((u16)(bb.x & 0xffff));
+    b4[1] = bf2f((u16)(bb.x >> 16));
+    b4[2] = bf2f((u16)(bb.y & 0xffff));
+    b4[3] = bf2f((u16)(bb.y >> 16));
+  }
+  const float v0 = epilogue(acc.x, 1.0f, b4[0], epi), v1 = epilogue(acc.y, 1.0f, b4[1], epi);
+  const float v2 = epilogue(acc.z, 1.0f, b4[2], epi), v3 = epilogue(acc.w, 1.0f, b4[3], epi);
+  if (out_f32) {
+    *(float4*)((float*)out + idx) = make_float4(v0, v1, v2, v3);
+  } else {
+    uint2 pk;
+    pk.x = pack_bf16x2(v0, v1);
+    pk.y = pack_bf16x2(v2, v3);
+    *(uint2*)((u16*)out + idx) = pk;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------
 static int check_hip(hipError_t e, const char* what) {
@@ -828,7 +869,7 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   int group_m = 4;
   if (group_m > tiles_m) group_m = tiles_m;
-  dim3 grid(p.grid[0], 1, p.grid[2]), block(WGM * WGN * 64);
+  dim3 grid(p.grid[0], p.split_k > 1 ? p.split_k : 1, p.grid[2]), block(WGM * WGN * 64);
   if (p.residue_copy)
     hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
                        tiles_n, group_m);
@@ -889,27 +930,47 @@ using namespace nimble;
 
 extern "C" {
 
+// One planned launch of dense; a K-split plan runs the slices into the workspace and then the
+// reduction kernel.
+static int run_dense(const GemmArgs& g, const nimble_plan& p, void* workspace, hipStream_t st) {
+  if (p.split_k <= 1 || p.variant < NIMBLE_VAR_T128x128) return launch_gemm(g, p, st);
+  GemmArgs part = g;
+  part.c = workspace;
+  part.out_f32 = 1;
+  part.epilogue = NIMBLE_EPI_NONE;
+  part.alpha = 1.0f;
+  part.bias = nullptr;
+  int rc = launch_gemm(part, p, st);
+  if (rc != NIMBLE_OK) return rc;
+  const long long quads = ((long long)g.M * g.N + 3) / 4;
+  dim3 grid((unsigned)((quads + 255) / 256)), block(256);
+  hipLaunchKernelGGL(splitk_reduce_kernel, grid, block, 0, st, (const float*)workspace, p.split_k,
+                     (long long)g.M * g.N, g.M, g.N, (const u16*)g.bias, g.epilogue, g.c, g.out_f32);
+  return check_hip(hipGetLastError(), "split-K reduction launch");
+}
+
 int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
                      int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
                      void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
-  (void)workspace;
   if (M < 0 || N < 0 || K < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
     return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
   if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32)
     return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  if (workspace_bytes > 0 && !workspace) return fail(NIMBLE_ERR_NULL, "workspace_bytes > 0 with a null workspace");
+  if (workspace && misaligned(workspace)) return fail(NIMBLE_ERR_ALIGN, "workspace must be 16-byte aligned");
+  // the dispatch function plans within the scratch the caller brought: no scratch, no K split
+  PlanOptions opt;
+  opt.max_workspace = workspace_bytes;
   nimble_plan p;
-  int rc = plan_dense(1, M, N, K, epilogue, force_variant, &p);
+  int rc = plan_dense(1, M, N, K, epilogue, force_variant, opt, &p);
   if (rc != NIMBLE_OK) return rc;
   if (M == 0 || N == 0) return NIMBLE_OK;
   if (!x || !w || !y) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
   if (epilogue != NIMBLE_EPI_NONE && !bias) return fail(NIMBLE_ERR_NULL, "epilogue needs a bias");
   if (misaligned(x) || misaligned(w) || misaligned(y) || (bias && misaligned(bias)))
     return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
-  if (workspace_bytes < p.workspace_bytes)
-    return fail(NIMBLE_ERR_WORKSPACE, "workspace of %zu bytes, plan needs %llu", workspace_bytes,
-                (unsigned long long)p.workspace_bytes);
   GemmArgs g{};
   g.a = x;
   g.b = w;
@@ -925,22 +986,24 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
   g.epilogue = epilogue;
   g.out_f32 = out_dtype == NIMBLE_F32;
   g.batch = 1;
-  if (p.split_rows <= 0) return launch_gemm(g, p, (hipStream_t)stream);
+  if (p.split_rows <= 0) return run_dense(g, p, workspace, (hipStream_t)stream);
 
-  // x = bm*k + r dispatched as two launches: rows [0, bm*k) through the r = 0 copy, then the
-  // r residue rows through the variant the plan chose for them
+  // two launches: rows [0, split_rows) through the r = 0 copy, then the remaining rows through
+  // whatever the dispatch function picks for their number (planned without a further row split)
   nimble_plan rp;
-  rc = plan_dense(1, M - p.split_rows, N, K, epilogue, p.residue_variant, &rp);
+  PlanOptions tail_opt = opt;
+  tail_opt.allow_row_split = false;
+  rc = plan_dense(1, M - p.split_rows, N, K, epilogue, NIMBLE_VAR_AUTO, tail_opt, &rp);
   if (rc != NIMBLE_OK) return rc;
   GemmArgs head = g;
   head.M = (int)p.split_rows;
-  rc = launch_gemm(head, p, (hipStream_t)stream);
+  rc = run_dense(head, p, workspace, (hipStream_t)stream);
   if (rc != NIMBLE_OK) return rc;
   GemmArgs tail = g;
   tail.M = (int)(M - p.split_rows);
   tail.a = (const u16*)x + p.split_rows * K;
   tail.c = g.out_f32 ? (void*)((float*)y + p.split_rows * N) : (void*)((u16*)y + p.split_rows * N);
-  return launch_gemm(tail, rp, (hipStream_t)stream);
+  return run_dense(tail, rp, workspace, (hipStream_t)stream);
 }
 
 int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch, int64_t M,
@@ -981,7 +1044,7 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
   g.batch = (int)batch;
   // batch slices of a K-contiguous operand stay 16-byte aligned only if M*K (N*K) is a multiple of 8
   if (p.variant != NIMBLE_VAR_GENERIC && (((M * K) & 7) != 0 || ((N * K) & 7) != 0)) {
-    rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, &p);
+    rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), &p);
     if (rc != NIMBLE_OK) return rc;
   }
   return launch_gemm(g, p, (hipStream_t)stream);

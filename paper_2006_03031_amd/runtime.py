@@ -49,6 +49,22 @@ class StorageArena:
         return flat.view(_TORCH_DTYPE[dtype]).view(tuple(shape))
 
 
+_WORKSPACE = {}
+WORKSPACE_BYTES = 64 << 20
+
+
+def default_workspace(device) -> torch.Tensor:
+    """Caller-owned scratch handed to every dense call (the library never allocates): holds the
+    f32 partial sums when the dispatch function cuts K.  One per device, shared by the calls on
+    one stream; calls that overlap on different streams must bring their own."""
+    key = str(device)
+    ws = _WORKSPACE.get(key)
+    if ws is None:
+        ws = torch.empty(WORKSPACE_BYTES, dtype=torch.uint8, device=device)
+        _WORKSPACE[key] = ws
+    return ws
+
+
 def _alloc(shape, dtype: int, device) -> torch.Tensor:
     # alloc_storage(size, alignment, device) + alloc_tensor(storage, 0, shape, dtype):
     # torch's caching allocator returns storage aligned to at least 512 bytes.
@@ -58,7 +74,8 @@ def _alloc(shape, dtype: int, device) -> torch.Tensor:
 
 def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilogue: int = nb.EPI_BIAS,
           out_dtype: int = nb.BF16, force_variant: int = nb.VAR_AUTO,
-          out: Optional[torch.Tensor] = None, arena: Optional[StorageArena] = None) -> torch.Tensor:
+          out: Optional[torch.Tensor] = None, arena: Optional[StorageArena] = None,
+          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     M, N = nb.nimble_dense_shape(tuple(x.shape), tuple(w.shape))
     K = x.shape[1]
     if out is not None:
@@ -67,8 +84,10 @@ def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilog
         y = arena.alloc((M, N), out_dtype)
     else:
         y = _alloc((M, N), out_dtype, x.device)
+    ws = workspace if workspace is not None else default_workspace(x.device)
     nb.nimble_dense_dyn(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else 0,
-                        y.data_ptr(), M, N, K, epilogue, out_dtype, force_variant, 0, 0, _stream())
+                        y.data_ptr(), M, N, K, epilogue, out_dtype, force_variant, ws.data_ptr(),
+                        ws.numel() * ws.element_size(), _stream())
     return y
 
 

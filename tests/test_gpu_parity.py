@@ -97,6 +97,30 @@ def test_tiled_variants_ragged_N_and_K(rt, nb, variant):
     _sweep(rt, nb, variant, N=bn + 6, K=1024, Ms=Ms, epilogue="bias", out_dtype=1)
 
 
+def test_split_k_forced_and_auto(rt, nb):
+    # forced: every ring variant, several slice counts, residues along M, both output types
+    for variant, (bm, bn) in ((4, (128, 128)), (5, (256, 128)), (6, (256, 256))):
+        for sk in (2, 4, 8):
+            forced = variant | (sk << 8)
+            _sweep(rt, nb, forced, N=bn, K=1024, Ms=[1, bm - 1, bm, bm + 3, 2 * bm + 1], epilogue="bias_gelu")
+        _sweep(rt, nb, variant | (3 << 8), N=2 * bn, K=32 * 13, Ms=[70, bm + 70], epilogue="bias", out_dtype=1)
+    # auto: mid-size M with long K and few tiles is where the dispatch function cuts K
+    for (M, N, K) in [(100, 768, 3072), (300, 768, 3072), (512, 768, 3072)]:
+        assert nb.dense_plan(M, N, K).split_k > 1
+    _sweep(rt, nb, -1, N=768, K=3072, Ms=[65, 100, 129, 300, 511, 512], epilogue="bias")
+    # no workspace: the same shapes must still run (the plan falls back to one launch)
+    import torch as _t
+    empty = _t.empty(0, dtype=_t.uint8, device="cuda")
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(77)
+    x, w, b = wl.uniform_bf16(rng, (300, 3072)), wl.normal_bf16(rng, (768, 3072)), wl.uniform_bf16(rng, (768,))
+    y = rt.dense(to_dev(x), to_dev(w), to_dev(b), nb.EPI_BIAS, workspace=empty)
+    assert _err(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias")) <= TOL
+    with pytest.raises(nb.NimbleError) as e:  # a forced split that does not fit is refused, not shrunk
+        rt.dense(to_dev(x), to_dev(w), to_dev(b), nb.EPI_BIAS, force_variant=4 | (4 << 8), workspace=empty)
+    assert e.value.code == -6
+
+
 def test_skinny_every_M_and_ragged_shapes(rt, nb):
     _sweep(rt, nb, 1, N=2048, K=1024, Ms=range(1, 65))
     _sweep(rt, nb, 1, N=128, K=128, Ms=range(1, 131), epilogue="bias")      # M > 64: several row blocks
