@@ -95,6 +95,7 @@ def load():
     lib.nimble_batch_matmul_dyn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_float, i32, vp,
                                             ctypes.c_size_t, vp]
     lib.nimble_softmax_rows_dyn.argtypes = [vp, vp, i64, i64, vp]
+    lib.nimble_attention_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.c_float, vp]
     lib.nimble_lstm_gates_dyn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
@@ -212,6 +213,11 @@ def nimble_batch_matmul_dyn(a: int, b: int, c: int, batch: int, M: int, N: int, 
 
 def nimble_softmax_rows_dyn(s_f32: int, p_bf16: int, rows: int, cols: int, stream: int = 0) -> None:
     _check(load().nimble_softmax_rows_dyn(s_f32, p_bf16, rows, cols, stream))
+
+
+def nimble_attention_dyn(q: int, k: int, v: int, o: int, heads: int, L: int, D: int, alpha: float,
+                         stream: int = 0) -> None:
+    _check(load().nimble_attention_dyn(q, k, v, o, heads, L, D, alpha, stream))
 
 
 def nimble_lstm_gates_dyn(x: int, h_prev: int, w: int, bias: int, c_prev: int, c_out: int, h_out: int,

@@ -20,6 +20,7 @@
 //       epilogue.
 //   generic_kernel            any shape and stride, one thread per output.
 //   softmax_rows_kernel       f32 scores -> bf16 probabilities, one wave per row.
+//   attention64_kernel        fused softmax(alpha Q.K^T).V for head dimension 64.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -805,6 +806,129 @@ __global__ void __launch_bounds__(256)
 }
 
 // ---------------------------------------------------------------------------
+// Fused attention for head dimension 64: O = softmax(alpha Q.K^T) V per head, in one launch,
+// the scores never leave the chip.  A workgroup owns 64 query rows of one head (16 per wave)
+// and walks the keys in blocks of 64 with a running row maximum and row sum.
+//   scores:  MFMA 16x16x32 with 16 key rows on the A side and the wave's 16 query rows on
+//            the B side: a lane holds, for its query row m = lane & 15, the keys
+//            16 t + 4 (lane >> 4) + v of key tile t (v = 0..3).
+//   P.V:     k runs over keys.  The sum over k does not care about order, so the 8 k-slots
+//            of lane group g in MFMA u are DEFINED as the 8 keys that group already holds:
+//            32u + 4g + (0..3) and 32u + 16 + 4g + (0..3).  P then goes from the score
+//            accumulators to the MFMA operand without leaving the lane; V is staged in LDS
+//            transposed ([d][key]) so the matching 8 values are two 8-byte reads.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+    attention64_kernel(const u16* __restrict__ q, const u16* __restrict__ k, const u16* __restrict__ v,
+                       u16* __restrict__ o, int L, float alpha) {
+  constexpr int D = 64, BJ = 64, VT_LD = 68;  // V^T rows padded to 68 elements against bank conflicts
+  __shared__ __attribute__((aligned(16))) uint4 Ks[BJ * 8];  // [key][8 chunks], chunk c at c ^ ((key >> 1) & 7)
+  __shared__ __attribute__((aligned(16))) u16 Vt[D * VT_LD];  // [d][key]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const long long head = (long long)blockIdx.y * L * D;
+  const int m_row = blockIdx.x * 64 + wave * 16 + r;
+  const int m_ld = m_row < L ? m_row : L - 1;
+
+  // the wave's query fragments: row m, d = 32 kk + 8 g .. + 7
+  bf16x8 qf[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk)
+    qf[kk] = as_bf16x8(*(const uint4*)(q + head + (long long)m_ld * D + kk * 32 + g * 8));
+
+  f32x4 oacc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) oacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float row_max = -INFINITY, row_sum = 0.f;  // row_sum: this lane's share, reduced at the end
+
+  for (int j0 = 0; j0 < L; j0 += BJ) {
+    __syncthreads();  // the previous block's fragments have been read
+    // stage K (row-major, swizzled) and V (transposed): 512 chunks of 16 bytes each, 2 per thread
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = tid + i * 256;
+      const int row = idx >> 3, c = idx & 7;
+      const int jr = (j0 + row < L) ? (j0 + row) : (L - 1);
+      const uint4 kc = *(const uint4*)(k + head + (long long)jr * D + c * 8);
+      Ks[row * 8 + (c ^ ((row >> 1) & 7))] = kc;
+      const uint4 vc = *(const uint4*)(v + head + (long long)jr * D + c * 8);
+      const u16* ve = (const u16*)&vc;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VT_LD + row] = ve[e];
+    }
+    __syncthreads();
+
+    // scores of the wave's 16 rows against the 64 keys of the block
+    f32x4 sacc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      sacc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int krow = t * 16 + r;
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 kf = as_bf16x8(Ks[krow * 8 + ((kk * 4 + g) ^ ((krow >> 1) & 7))]);
+        sacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[kk], sacc[t], 0, 0, 0);
+      }
+    }
+    // scale, mask keys past L, block maximum of the row (4 lanes share a row)
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + t * 16 + g * 4 + e;
+        const float sv = (j < L) ? alpha * sacc[t][e] : -INFINITY;
+        sacc[t][e] = sv;
+        bmax = fmaxf(bmax, sv);
+      }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+    const float new_max = fmaxf(row_max, bmax);  // finite: key j0 < L is in every block
+    const float rescale = __expf(row_max - new_max);
+    row_max = new_max;
+    row_sum *= rescale;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float pv = __expf(sacc[t][e] - new_max);
+        sacc[t][e] = pv;
+        row_sum += pv;
+        oacc[t][e] *= rescale;
+      }
+    // O += P.V: MFMA u consumes key tiles 2u and 2u+1
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      uint4 pw;
+      pw.x = pack_bf16x2(sacc[2 * u][0], sacc[2 * u][1]);
+      pw.y = pack_bf16x2(sacc[2 * u][2], sacc[2 * u][3]);
+      pw.z = pack_bf16x2(sacc[2 * u + 1][0], sacc[2 * u + 1][1]);
+      pw.w = pack_bf16x2(sacc[2 * u + 1][2], sacc[2 * u + 1][3]);
+      const bf16x8 pf = as_bf16x8(pw);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const u16* vrow = Vt + (t * 16 + r) * VT_LD + u * 32 + g * 4;
+        const uint2 lo = *(const uint2*)vrow, hi = *(const uint2*)(vrow + 16);
+        const bf16x8 vf = as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+        oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, oacc[t], 0, 0, 0);
+      }
+    }
+  }
+  row_sum += __shfl_xor(row_sum, 16, 64);
+  row_sum += __shfl_xor(row_sum, 32, 64);
+  const float inv = 1.0f / row_sum;
+  if (m_row < L) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      uint2 pk;
+      pk.x = pack_bf16x2(oacc[t][0] * inv, oacc[t][1] * inv);
+      pk.y = pack_bf16x2(oacc[t][2] * inv, oacc[t][3] * inv);
+      *(uint2*)(o + head + (long long)m_row * D + t * 16 + g * 4) = pk;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Second half of a K-split launch: add the `slices` f32 partial planes, apply the epilogue,
 // write the output.  One thread per 4 consecutive columns (N is a multiple of 128 here).
 // ---------------------------------------------------------------------------
@@ -1063,6 +1187,22 @@ int nimble_softmax_rows_dyn(const void* s_f32, void* p_bf16, int64_t rows, int64
   hipLaunchKernelGGL(softmax_rows_kernel, grid, block, 0, (hipStream_t)stream, (const float*)s_f32,
                      (u16*)p_bf16, (long long)rows, (int)cols);
   return check_hip(hipGetLastError(), "softmax kernel launch");
+}
+
+int nimble_attention_dyn(const void* q, const void* k, const void* v, void* o, int64_t heads, int64_t L,
+                         int64_t D, float alpha, void* stream) {
+  clear_error();
+  if (heads < 0 || L < 0 || D < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  if (D != 64) return fail(NIMBLE_ERR_ARG, "fused attention is built for head dimension 64, got %lld", (long long)D);
+  if (heads > 65535 || L > (1ll << 24)) return fail(NIMBLE_ERR_ARG, "extent too large");
+  if (heads == 0 || L == 0) return NIMBLE_OK;
+  if (!q || !k || !v || !o) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  dim3 grid((unsigned)((L + 63) / 64), (unsigned)heads), block(256);
+  hipLaunchKernelGGL(attention64_kernel, grid, block, 0, (hipStream_t)stream, (const u16*)q, (const u16*)k,
+                     (const u16*)v, (u16*)o, (int)L, alpha);
+  return check_hip(hipGetLastError(), "attention kernel launch");
 }
 
 int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, const void* bias,

@@ -118,6 +118,17 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     return s, p, o
 
 
+def fused_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, alpha: float = 0.125,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """O = softmax(alpha Q.K^T).V in one launch.  The composite's shape function is the two
+    batch_matmul shape functions connected: (T,L,D)x(T,L,D)^T -> (T,L,L), then x(T,L,D) -> (T,L,D)."""
+    s_shape = nb.batch_matmul_shape(tuple(q.shape), tuple(k.shape), True)
+    T, L, D = nb.batch_matmul_shape(s_shape, tuple(v.shape), False)
+    o = out if out is not None else _alloc((T, L, D), nb.BF16, q.device)
+    nb.nimble_attention_dyn(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), T, L, D, alpha, _stream())
+    return o
+
+
 def lstm_step(x: torch.Tensor, h: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, c: torch.Tensor,
               h_out: Optional[torch.Tensor] = None,
               c_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:

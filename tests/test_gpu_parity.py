@@ -329,6 +329,32 @@ def test_attention_chain(rt, nb):
             assert np.array_equal(from_dev(o), v.f32)
 
 
+def test_fused_attention_matches_the_oracle_chain(rt, nb):
+    to_dev, _, from_dev, _ = _dev()
+    Ls = sorted(set([1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 300, 511, 512] +
+                    [int(v) for v in wl.config4_lengths()[:12]]))
+    for d, L in enumerate(Ls):
+        q, k, v = wl.config4_qkv(100 + d, L)
+        buf = torch.full((12, L + 1, 64), 768.0, dtype=torch.bfloat16, device="cuda")  # one guard row after the last head
+        o = rt.fused_attention(to_dev(q), to_dev(k), to_dev(v))
+        assert tuple(o.shape) == (12, L, 64)
+        _, _, ro = oracle.attention(q.f32, k.f32, v.f32)
+        assert _err(from_dev(o), ro) <= TOL, ("O", L)
+        # and it agrees with the three-call chain on the GPU to rounding
+        _, _, o3 = rt.attention(to_dev(q), to_dev(k), to_dev(v))
+        assert _err(from_dev(o), from_dev(o3)) <= TOL, ("O vs chain", L)
+    # closed forms: L = 1 returns V; Q = 0 returns the column mean of V
+    q, k, v = wl.config4_qkv(7, 1)
+    assert np.array_equal(from_dev(rt.fused_attention(to_dev(q), to_dev(k), to_dev(v))), v.f32)
+    q, k, v = wl.config4_qkv(8, 8)
+    zq = wl.BF16Array(np.zeros_like(q.bits), np.zeros_like(q.f32))
+    o = from_dev(rt.fused_attention(to_dev(zq), to_dev(k), to_dev(v)))
+    assert np.max(np.abs(o - v.f32.astype(np.float64).mean(axis=1, keepdims=True))) < 4e-3
+    with pytest.raises(nb.NimbleError) as e:  # other head dimensions go through the three calls
+        nb.nimble_attention_dyn(1 << 8, 1 << 8, 1 << 8, 1 << 8, 12, 5, 32, 0.125)
+    assert e.value.code == -8
+
+
 def test_batch_matmul_general_shapes(rt, nb):
     to_dev, _, from_dev, _ = _dev()
     rng = np.random.default_rng(9)
