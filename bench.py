@@ -162,7 +162,34 @@ def small_m_probe():
         torch.cuda.synchronize()
         us = s.elapsed_time(e) * 1e3 / 128
         nbytes = 2048 * 1024 * 2 + 4096 + 7168 * B
-        out[f"lstm_step_B{B}_warm"] = {"us_per_step": round(us, 2), "eff_GBps": round(nbytes / us / 1e3, 1)}
+        # the same 128-step loop captured as a HIP graph (one graph per batch size)
+        seq = rt.LstmSequenceGraph(dw, db, B, 128, 512, 512)
+        seq.run()
+        torch.cuda.synchronize()
+        s.record()
+        for _ in range(4):
+            seq.graph.replay()
+        e.record()
+        torch.cuda.synchronize()
+        us_g = s.elapsed_time(e) * 1e3 / (4 * 128)
+        out[f"lstm_step_B{B}_warm"] = {"us_per_step": round(us, 2), "us_per_step_graph": round(us_g, 2),
+                                       "eff_GBps_graph": round(nbytes / us_g / 1e3, 1)}
+    # attention, 12 heads x 64, one launch versus the three-call chain
+    for L in (128, 512):
+        q = torch.empty((12, L, 64), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        k, v, o = q.clone(), q.clone(), torch.empty_like(q)
+        res = {}
+        for name, fn, reps in (("fused", lambda: rt.fused_attention(q, k, v, out=o), 64),
+                               ("chain", lambda: rt.attention(q, k, v), 16)):
+            fn()
+            torch.cuda.synchronize()
+            s.record()
+            for _ in range(reps):
+                fn()
+            e.record()
+            torch.cuda.synchronize()
+            res[name + "_us"] = round(s.elapsed_time(e) * 1e3 / reps, 2)
+        out[f"attention_L{L}"] = res
     return out
 
 

@@ -630,6 +630,22 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
   const int M = s.M, N = s.N, K = s.K;
   const int mbase = blockIdx.y * 64;
 
+  // operands of the epilogue, fetched first so their latency hides behind the weight stream
+  float pre_bias[4] = {0.f, 0.f, 0.f, 0.f};
+  float pre_c = 0.f;
+  if (LSTM) {
+    const int t = tid >> 6, mm = (tid & 63) >> 2, u = tid & 3;
+    const int m = mbase + t * 16 + mm, unit = blockIdx.x * 4 + u;
+    if (t < MT && m < M && unit < s.H) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) pre_bias[q] = bf2f(s.bias[q * s.H + unit]);
+      pre_c = s.c_prev[(long long)m * s.H + unit];
+    }
+  } else {
+    const int n = blockIdx.x * 16 + (tid & 15);
+    if (n < N && s.epilogue != NIMBLE_EPI_NONE) pre_bias[0] = bf2f(s.bias[n]);
+  }
+
   // weight row of this lane
   long long wrow;
   if (LSTM) {
@@ -717,10 +733,10 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
           const int col = q * 4 + u;
           const float sum = (red[0][t][mm][col] + red[1][t][mm][col]) +
                             (red[2][t][mm][col] + red[3][t][mm][col]);
-          gate[q] = sum + bf2f(s.bias[q * s.H + unit]);
+          gate[q] = sum + pre_bias[q];
         }
         const long long o = (long long)m * s.H + unit;
-        const float cn = sigmoidf(gate[1]) * s.c_prev[o] + sigmoidf(gate[0]) * tanhf(gate[2]);
+        const float cn = sigmoidf(gate[1]) * pre_c + sigmoidf(gate[0]) * tanhf(gate[2]);
         s.c_out[o] = cn;
         ((u16*)s.y)[o] = f2bf(sigmoidf(gate[3]) * tanhf(cn));
       }
@@ -729,7 +745,7 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
     const int mm = tid >> 4, nn = tid & 15;
     const int n = blockIdx.x * 16 + nn;
     if (n < N) {
-      const float b = (s.epilogue != NIMBLE_EPI_NONE) ? bf2f(s.bias[n]) : 0.f;
+      const float b = pre_bias[0];
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
         const int m = mbase + t * 16 + mm;

@@ -141,3 +141,42 @@ def lstm_step(x: torch.Tensor, h: torch.Tensor, w: torch.Tensor, bias: torch.Ten
     nb.nimble_lstm_gates_dyn(x.data_ptr(), h.data_ptr(), w.data_ptr(), bias.data_ptr(), c.data_ptr(),
                              c_out.data_ptr(), h_out.data_ptr(), B, Ix, H, 0, 0, _stream())
     return h_out, c_out
+
+
+class LstmSequenceGraph:
+    """The token loop of one sequence, `steps` launches of the fused LSTM cell, captured once
+    per batch size B as a HIP graph and replayed: the loop is launch-bound (a step is a few
+    microseconds of GPU work), so replaying removes the per-step host cost.  The graph holds
+    kernel launches only (state is cleared by a fill kernel outside it).  The dynamic extent
+    B is fixed per graph; a server keeps one graph per batch size it has seen."""
+
+    def __init__(self, w: torch.Tensor, bias: torch.Tensor, B: int, steps: int, Ix: int, H: int):
+        dev = w.device
+        (self.B, self.H), _ = nb.lstm_shape((B, Ix), (B, H), (B, H), tuple(w.shape))
+        self.steps, self.Ix = steps, Ix
+        self.w, self.bias = w, bias
+        self.xs = torch.zeros((steps, B, Ix), dtype=torch.bfloat16, device=dev)
+        self.hs = torch.zeros((steps + 1, B, H), dtype=torch.bfloat16, device=dev)  # hs[0] = h_0
+        self.c = torch.zeros((B, H), dtype=torch.float32, device=dev)
+        # one eager pass so that nothing is lazily initialised during capture
+        self._enqueue()
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self._enqueue()
+
+    def _enqueue(self) -> None:
+        st = _stream()
+        for t in range(self.steps):
+            nb.nimble_lstm_gates_dyn(self.xs[t].data_ptr(), self.hs[t].data_ptr(), self.w.data_ptr(),
+                                     self.bias.data_ptr(), self.c.data_ptr(), self.c.data_ptr(),
+                                     self.hs[t + 1].data_ptr(), self.B, self.Ix, self.H, 0, 0, st)
+
+    def run(self, xs: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+        """Run the sequence from h_0 = c_0 = 0; returns (all h_t [steps,B,H], final c)."""
+        if xs is not None:
+            self.xs.copy_(xs)
+        self.hs[0].zero_()
+        self.c.zero_()
+        self.graph.replay()
+        return self.hs[1:], self.c

@@ -309,6 +309,37 @@ def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
         assert _err(from_dev(cg), rc) <= TOL and _err(from_dev(hg), rh) <= TOL, (B2, H2, Ix2)
 
 
+def test_lstm_sequence_graph_replays_match_eager(rt, nb):
+    """The captured token loop is replayed several times, with eager work and synchronisation in
+    between, and every replay must reproduce the eager step-by-step result bit for bit."""
+    to_dev, f32_to_dev, from_dev, bits_from_dev = _dev()
+    lw = wl.config2_weights()
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    H, steps = wl.LSTM_H, 12
+    for B in (3, 40):
+        seq = rt.LstmSequenceGraph(dw, db, B, steps, wl.LSTM_IX, H)
+        for rep in range(3):
+            xs = wl.config2_inputs(50 + rep, B, steps)
+            xd = to_dev(xs)
+            # eager reference on the GPU
+            h = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
+            c = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+            eager = []
+            for t in range(steps):
+                h, c = rt.lstm_step(xd[t], h, dw, db, c)
+                eager.append(bits_from_dev(h))
+            torch.cuda.synchronize()
+            hs, c_fin = seq.run(xd)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits_from_dev(hs), np.stack(eager)), (B, rep)
+            assert np.array_equal(from_dev(c_fin), from_dev(c)), (B, rep)
+        # first step against the oracle (h_0 = c_0 = 0)
+        x0 = wl.BF16Array(xs.bits[0], xs.f32[0])
+        rh, rc = oracle.lstm_step(x0.f32, np.zeros((B, H), np.float32), lw.w.f32, lw.b.f32,
+                                  np.zeros((B, H), np.float32))
+        assert _err(from_dev(hs[0]), rh) <= TOL
+
+
 # ------------------------------------------------------------------ config 4
 def test_attention_chain(rt, nb):
     to_dev, _, from_dev, _ = _dev()
