@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libnimble_hip.so")
-SOURCES = ["nimble_host.cpp", "nimble_kernels.hip"]
+SOURCES = ["nimble_host.cpp", "nimble_kernels.hip"]  # the .h files under csrc/ hold the kernels
 
 
 def hipcc_command(out: str = LIB):

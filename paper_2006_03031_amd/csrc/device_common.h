@@ -1,0 +1,107 @@
+// Device-side helpers shared by every kernel: bf16 conversion, the dense epilogue, direct
+// global->LDS loads, the workgroup-to-tile map.
+#ifndef NIMBLE_DEVICE_COMMON_H_
+#define NIMBLE_DEVICE_COMMON_H_
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "nimble_internal.h"
+
+namespace nimble {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf2f(u16 b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// float32 -> bfloat16, round to nearest, ties to even.
+__device__ __forceinline__ u16 f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+// erf(|x|) by the rational-times-Gaussian form of Abramowitz & Stegun 7.1.26
+// (|error| <= 1.5e-7), on the hardware exp2 and reciprocal: about a dozen
+// instructions where the library erff costs several times that, which matters
+// when the epilogue runs once per output element.
+// gelu(v) = v/2 (1 + erf(v / sqrt 2)) = v/2 + |v/2| erf(|v| / sqrt 2)
+__device__ __forceinline__ float gelu_erf(float v) {
+  const float ax = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f(v * v * -0.72134752044448170f);  // exp(-v^2 / 2)
+  const float r = fmaf(-p, e, 1.0f);                                       // erf(|v| / sqrt 2)
+  const float hv = 0.5f * v;
+  return fmaf(fabsf(hv), r, hv);
+}
+
+__device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+__device__ __forceinline__ float epilogue(float acc, float alpha, float bias, int epi) {
+  float v = alpha * acc;
+  if (epi != NIMBLE_EPI_NONE) v += bias;
+  if (epi == NIMBLE_EPI_BIAS_GELU_ERF) v = gelu_erf(v);
+  return v;
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Two float32 -> two bfloat16 (round to nearest even) in one v_cvt_pk_bf16_f32; lo in bits 0..15.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte
+// address lds_addr + 16 i (lds_addr is wave-uniform and goes through M0).  It is
+// tracked by vmcnt only; the caller waits with s_waitcnt vmcnt before a barrier
+// makes the data visible to the other waves.  Written as inline assembly so that
+// the compiler does not serialise it against LDS reads of the other ring slots.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_addr)
+               : "memory", "m0");
+}
+// Same, addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit per-lane
+// byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
+__device__ __forceinline__ void dma16_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase),
+               "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+// ---------------------------------------------------------------------------
+// Workgroup id -> macro tile.  Workgroups are handed to the 8 XCDs round robin;
+// give each XCD a contiguous run of tile ids so that the tiles sharing rows of
+// A and B meet in that XCD's L2, and walk the tiles in groups of `group_m`
+// tile rows so that the set in flight is a compact block.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n,
+                                              int group_m, int& tm, int& tn) {
+  const int q = nblocks >> 3, rem = nblocks & 7;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int pid = xcd * q + (xcd < rem ? xcd : rem) + local;
+  const int in_group = group_m * tiles_n;
+  const int gid = pid / in_group;
+  const int first_m = gid * group_m;
+  const int gsize = (tiles_m - first_m) < group_m ? (tiles_m - first_m) : group_m;
+  const int rest = pid - gid * in_group;
+  tm = first_m + rest % gsize;
+  tn = rest / gsize;
+}
+
+}  // namespace nimble
+#endif

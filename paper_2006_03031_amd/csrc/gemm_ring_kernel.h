@@ -1,0 +1,326 @@
+// Large-tile MFMA kernel: ring of direct global->LDS stages, 16x16x32 MFMA, LDS-transposed epilogue,
+// split-K reduction.
+#ifndef NIMBLE_GEMM_RING_KERNEL_H_
+#define NIMBLE_GEMM_RING_KERNEL_H_
+#include "device_common.h"
+#include "gemm_tile_kernel.h"
+
+namespace nimble {
+
+// ---------------------------------------------------------------------------
+// Interior body of the large tiles.
+//   LDS: a ring of S = 4 stages, each BM + BN rows of 32 bf16 (4 chunks of 16
+//   bytes); chunk c of row r sits at slot c ^ ((r >> 2) & 3), so that the 16
+//   rows one quarter-wave reads at one logical chunk cover all 64 banks.
+//   Every wave issues its share of each stage as 16-byte-per-lane direct
+//   global->LDS loads (a wave instruction fills 16 rows x 64 bytes = 1 KiB of
+//   contiguous LDS); the swizzle is applied on the global side by choosing
+//   which chunk a lane fetches.
+//   Step ks: wait until this wave's loads of stage ks+1 have landed, barrier
+//   (now every wave's have, and every wave has finished reading stage ks-1),
+//   refill the slot of stage ks-1 with stage ks+3, read the fragments of stage
+//   ks+1 into the second register set, run the MFMAs of stage ks.
+//   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
+//   activation rows (m); a lane ends up with 4 consecutive n of one row m.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, bool MEDGE, bool PINGPONG>
+__device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
+                                               uint4* smem) {
+  constexpr int S = 4;
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 16, TN = WN / 16;
+  constexpr int A_LD = BM * 4 / NT, B_LD = BN * 4 / NT;
+  constexpr int LD = A_LD + B_LD;
+  static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the workgroup");
+  static_assert(WN == 64, "the LDS epilogue assumes 64 output columns per wave");
+  static_assert(NW * WM * WN * 2 <= S * (BM + BN) * 64, "epilogue staging does not fit in the ring");
+  uint4(*As)[BM * 4] = reinterpret_cast<uint4(*)[BM * 4]>(smem);
+  uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BM * 4);
+
+  // gridDim.y > 1: K is cut into gridDim.y slices of whole stages; slice blockIdx.y writes its
+  // f32 partial sums to its own [M,N] plane of the output (g.c is then the split-K workspace)
+  const int z = blockIdx.z;
+  const int stages_all = g.K >> 5;
+  const int stages_per = (stages_all + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int stage0 = (int)blockIdx.y * stages_per;
+  const int KS = (stages_all - stage0) < stages_per ? (stages_all - stage0) : stages_per;
+  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa + (stage0 << 5);
+  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb + (stage0 << 5);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // loads: pass i covers chunk ids i*NT + tid: row = i*(NT/4) + (tid >> 2), slot = tid & 3.
+  // Address = uniform base of (tile row 0, pass i, stage k0) + per-lane byte offset.
+  // MEDGE (the last tile along M when r != 0): rows past M-1 are fetched from row M-1, so
+  // every load stays in bounds; their products land in rows the epilogue never stores.
+  const int ld_row = tid >> 2;
+  const int ld_c = (tid & 3) ^ ((ld_row >> 2) & 3);
+  uint32_t a_off[A_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    int row = ld_row + i * (NT / 4);
+    if (MEDGE) row = (m0 + row < g.M) ? row : (g.M - 1 - m0);
+    a_off[i] = (uint32_t)(row * g.lda + ld_c * 8) * 2u;
+  }
+  const uint32_t b_off = (uint32_t)(ld_row * g.ldb + ld_c * 8) * 2u;
+  const u16* a_base = A + (long long)m0 * g.lda;
+  const u16* b_base = B + (long long)n0 * g.ldb;
+  const long long b_pass = (long long)(NT / 4) * g.ldb;
+  const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&As[0][wave * 64]));
+  const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&Bs[0][wave * 64]));
+  auto dma = [&](int ks, int slot) {
+    const int k0 = ks << 5;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i)
+      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BM * 64) + i * NT * 16);
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i)
+      dma16_so(b_off, b_base + i * b_pass + k0, b_dst + slot * (BN * 64) + i * NT * 16);
+  };
+
+  // fragment reads: lane -> row (lane & 15), logical chunk (lane >> 4)
+  const int fr_row = lane & 15;
+  const int fr_q = lane >> 4;
+  const int fr_phys = fr_q ^ ((fr_row >> 2) & 3);
+  const int fr_a = (wm * WM + fr_row) * 4 + fr_phys;
+  const int fr_b = (wn * WN + fr_row) * 4 + fr_phys;
+
+  f32x4 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int s = 0; s < S - 1; ++s)
+    if (s < KS) dma(s, s);
+
+  if (KS - 1 >= S - 2)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
+  else
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  if constexpr (PINGPONG) {
+    // Waves w and w + NW/2 share a SIMD.  The workgroup runs in two groups half a step out of
+    // phase: while group P multiplies stage s, group Q issues its loads and reads its fragments
+    // of stage s, then they swap.  A wave never has memory instructions and MFMAs queued
+    // together, and the matrix core of each SIMD always has one wave feeding it.
+    //   P:    mem(0) | mfma(0) | mem(1) | mfma(1) | ...        ("|" = workgroup barrier)
+    //   Q:  |        | mem(0)  | mfma(0)| mem(1)  | ...
+    // mem(s) refills the slot of stage s-1 (both groups finished reading it before the barrier
+    // that starts the phase) with stage s+3, then reads the fragments of stage s.  Before the
+    // barrier that precedes P's mem(s+1) every wave has waited for its own loads of stage s+1.
+    const bool is_q = wave >= NW / 2;
+    bf16x8 xa[TM], wb[TN];
+    if (is_q) __syncthreads();
+    for (int base = 0; base < KS; base += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u) {
+        const int ks = base + u;
+        if (ks < KS) {
+          const int slot = u % S, slot_free = (u + S - 1) % S;
+          if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
+#pragma unroll
+          for (int j = 0; j < TM; ++j) xa[j] = as_bf16x8(As[slot][fr_a + j * 64]);
+#pragma unroll
+          for (int i = 0; i < TN; ++i) wb[i] = as_bf16x8(Bs[slot][fr_b + i * 64]);
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          if (is_q && ks + 1 < KS) {
+            if (ks + S - 1 < KS)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_s_setprio(0);
+          if (!is_q && ks + 1 < KS) {
+            if (ks + S - 1 < KS)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    if (!is_q) __syncthreads();
+  } else {
+    bf16x8 xa[2][TM], wb[2][TN];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(As[0][fr_a + j * 64]);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(Bs[0][fr_b + i * 64]);
+
+    for (int base = 0; base < KS; base += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u) {  // unrolled: ring slot and register set are compile-time
+        const int ks = base + u;
+        if (ks < KS) {
+          const int cur = u & 1;
+          const int slot_next = (u + 1) % S, slot_free = (u + S - 1) % S;
+          if (ks + 1 < KS) {
+            // stage ks+1 may have min(S-3, KS-ks-2) younger stages still in flight behind it
+            if (KS - ks - 2 >= S - 3)
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
+            else
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) xa[cur ^ 1][j] = as_bf16x8(As[slot_next][fr_a + j * 64]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) wb[cur ^ 1][i] = as_bf16x8(Bs[slot_next][fr_b + i * 64]);
+          }
+#pragma unroll
+          for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+              acc[i][j] =
+                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
+  const float alpha = g.alpha;
+  const int epi = g.epilogue;
+  float bias4[TN][4];
+#pragma unroll
+  for (int i = 0; i < TN; ++i) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) bias4[i][v] = 0.f;
+    if (epi != NIMBLE_EPI_NONE) {
+      const uint2 bb = *(const uint2*)((const u16*)g.bias + n0 + wn * WN + i * 16 + fr_q * 4);
+      bias4[i][0] = bf2f((u16)(bb.x & 0xffff));
+      bias4[i][1] = bf2f((u16)(bb.x >> 16));
+      bias4[i][2] = bf2f((u16)(bb.y & 0xffff));
+      bias4[i][3] = bf2f((u16)(bb.y >> 16));
+    }
+  }
+  if (g.out_f32) {
+    float* C = (float*)g.c + (long long)z * g.sc + (long long)blockIdx.y * g.M * g.ldc;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      const int m = m0 + wm * WM + j * 16 + fr_row;
+      if (MEDGE && m >= g.M) continue;
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+        const int n = n0 + wn * WN + i * 16 + fr_q * 4;
+        float4 o;
+        o.x = epilogue(acc[i][j][0], alpha, bias4[i][0], epi);
+        o.y = epilogue(acc[i][j][1], alpha, bias4[i][1], epi);
+        o.z = epilogue(acc[i][j][2], alpha, bias4[i][2], epi);
+        o.w = epilogue(acc[i][j][3], alpha, bias4[i][3], epi);
+        *(float4*)(C + (long long)m * g.ldc + n) = o;
+      }
+    }
+    return;
+  }
+  // bf16: every wave stages its [WM][64] block in LDS (rows of 128 bytes, chunk c of
+  // row r at slot c ^ ((r >> 1) & 7)) and writes it back out as full 128-byte lines
+  __syncthreads();  // all fragment reads of the ring are done
+  unsigned char* region = (unsigned char*)smem + wave * (WM * WN * 2);
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int row = j * 16 + fr_row;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int col = i * 16 + fr_q * 4;
+      const int chunk = (col >> 3) ^ ((row >> 1) & 7);
+      uint2 pk;
+      pk.x = pack_bf16x2(epilogue(acc[i][j][0], alpha, bias4[i][0], epi),
+                         epilogue(acc[i][j][1], alpha, bias4[i][1], epi));
+      pk.y = pack_bf16x2(epilogue(acc[i][j][2], alpha, bias4[i][2], epi),
+                         epilogue(acc[i][j][3], alpha, bias4[i][3], epi));
+      *(uint2*)(region + row * 128 + chunk * 16 + (col & 4) * 2) = pk;
+    }
+  }
+  // the region is private to the wave: no workgroup barrier, the compiler orders the LDS accesses
+  u16* C = (u16*)g.c + (long long)z * g.sc;
+#pragma unroll
+  for (int p = 0; p < WM / 8; ++p) {
+    const int row = p * 8 + (lane >> 3);
+    const int c = lane & 7;
+    const uint4 v = *(const uint4*)(region + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
+    if (MEDGE && m0 + wm * WM + row >= g.M) continue;
+    *(uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + c * 8) = v;
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
+__global__ void __launch_bounds__(WGM* WGN * 64)
+    gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
+  // the two-group schedule pays off when a wave's multiply phase is long: 128x64 wave tiles
+  constexpr bool kPingPong = (BM / WGM) * (BN / WGN) >= 128 * 64 && WGM * WGN == 8;
+  __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  if (RESIDUE) {
+    // the packed epilogue needs 16-byte aligned output rows; K must be whole 32-wide stages
+    const bool ragged = (n0 + BN > g.N) || ((g.K & 31) != 0) || ((g.ldc & 7) != 0);
+    if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
+      gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      return;
+    }
+    if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
+      gemm_ring_body<BM, BN, WGM, WGN, true, kPingPong>(g, m0, n0, smem);
+      return;
+    }
+  }
+  gemm_ring_body<BM, BN, WGM, WGN, false, kPingPong>(g, m0, n0, smem);
+}
+
+// ---------------------------------------------------------------------------
+// Second half of a K-split launch: add the `slices` f32 partial planes, apply the epilogue,
+// write the output.  One thread per 4 consecutive columns (N is a multiple of 128 here).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+    splitk_reduce_kernel(const float* __restrict__ ws, int slices, long long plane, int M, int N,
+                         const u16* __restrict__ bias, int epi, void* __restrict__ out, int out_f32) {
+  const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= (long long)M * N) return;
+  float4 acc = *(const float4*)(ws + idx);
+  for (int s = 1; s < slices; ++s) {
+    const float4 v = *(const float4*)(ws + (long long)s * plane + idx);
+    acc.x += v.x;
+    acc.y += v.y;
+    acc.z += v.z;
+    acc.w += v.w;
+  }
+  float b4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (epi != NIMBLE_EPI_NONE) {
+    const uint2 bb = *(const uint2*)(bias + (int)(idx % N));
+    b4[0] = bf2f((u16)(bb.x & 0xffff));
+    b4[1] = bf2f((u16)(bb.x >> 16));
+    b4[2] = bf2f((u16)(bb.y & 0xffff));
+    b4[3] = bf2f((u16)(bb.y >> 16));
+  }
+  const float v0 = epilogue(acc.x, 1.0f, b4[0], epi), v1 = epilogue(acc.y, 1.0f, b4[1], epi);
+  const float v2 = epilogue(acc.z, 1.0f, b4[2], epi), v3 = epilogue(acc.w, 1.0f, b4[3], epi);
+  if (out_f32) {
+    *(float4*)((float*)out + idx) = make_float4(v0, v1, v2, v3);
+  } else {
+    uint2 pk;
+    pk.x = pack_bf16x2(v0, v1);
+    pk.y = pack_bf16x2(v2, v3);
+    *(uint2*)((u16*)out + idx) = pk;
+  }
+}
+
+}  // namespace nimble
+#endif
