@@ -75,8 +75,8 @@ static const double kLaunchGapUs = 4.0;
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
 // at the chip's power-limited rate; the last, partial round runs faster per tile the fewer
-// units it occupies (measured: about 0.62 of the full-round time when a handful of units
-// are busy, 0.72 at half the chip).  So a dynamic M just past a tile boundary costs most of
+// units it occupies (measured: about 0.6 of the full-round time when a handful of units
+// are busy, 0.8 at half the chip).  So a dynamic M just past a tile boundary costs most of
 // an extra round with big tiles, while smaller tiles quantise more finely but run the
 // matrix cores less efficiently.  Cutting K multiplies the tiles and shortens each; the
 // partial sums then cross HBM once more and a second small kernel adds them up.
@@ -95,7 +95,7 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
   double us = (double)full_rounds * t_full;
   if (rem > 0) {
     const double occ = (double)rem / (double)kCUs;
-    us += t_full * (0.62 + 0.38 * occ * occ);
+    us += t_full * (0.6 + 0.4 * occ);
   }
   if (sk > 1) us += kLaunchGapUs + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.0e6;
   return us;
