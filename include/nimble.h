@@ -145,6 +145,20 @@ int nimble_residue_split(int64_t x, int64_t tile, int64_t* k, int64_t* r);
 int nimble_dense_plan(int64_t M, int64_t N, int64_t K, int epilogue, int out_dtype,
                       int force_variant, nimble_plan* plan);
 
+/* Tuned dispatch table (Section 3.5, tuning for symbolic shapes: measure the candidate
+ * configurations offline on a grid of M and keep the best).  An entry overrides the built-in
+ * cost model for dense calls with the given (N, K, epilogue) and m_lo <= M <= m_hi: the call
+ * runs `variant` with K cut into `split_k` slices (1 = no cut) as one launch.  Entries that
+ * cannot run (workspace too small for the cut, K not a multiple of 8) are skipped at dispatch.
+ * `count` = 0 removes the table of that (N, K, epilogue).  Host only; not thread safe against
+ * concurrent dispatch.  Returns NIMBLE_OK or NIMBLE_ERR_ARG / NIMBLE_ERR_NULL. */
+typedef struct nimble_table_entry {
+  int64_t m_lo, m_hi;
+  int32_t variant, split_k;
+} nimble_table_entry;
+int nimble_dense_table_set(int64_t N, int64_t K, int epilogue, const nimble_table_entry* entries,
+                           int count);
+
 /* Same for one batch_matmul (grid z = batch). */
 int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b,
                              int out_dtype, nimble_plan* plan);

@@ -25,6 +25,11 @@ class NimbleError(RuntimeError):
         self.code = code
 
 
+class _CTableEntry(ctypes.Structure):
+    _fields_ = [("m_lo", ctypes.c_int64), ("m_hi", ctypes.c_int64), ("variant", ctypes.c_int32),
+                ("split_k", ctypes.c_int32)]
+
+
 class _CPlan(ctypes.Structure):
     _fields_ = [("variant", ctypes.c_int32), ("bm", ctypes.c_int32), ("bn", ctypes.c_int32),
                 ("bk", ctypes.c_int32), ("k", ctypes.c_int64), ("r", ctypes.c_int32),
@@ -88,6 +93,7 @@ def load():
     lib.nimble_dense_plan.argtypes = [i64, i64, i64, i32, i32, i32, ctypes.POINTER(_CPlan)]
     lib.nimble_batch_matmul_plan.argtypes = [i64, i64, i64, i64, i32, i32, ctypes.POINTER(_CPlan)]
     lib.nimble_lstm_plan.argtypes = [i64, i64, i64, ctypes.POINTER(_CPlan)]
+    lib.nimble_dense_table_set.argtypes = [i64, i64, i32, ctypes.POINTER(_CTableEntry), i32]
     lib.nimble_variant_name.argtypes = [i32]
     lib.nimble_variant_name.restype = ctypes.c_char_p
     lib.nimble_last_error.restype = ctypes.c_char_p
@@ -122,7 +128,20 @@ def _arr(shape: Sequence[int]):
 
 
 # ------------------------------------------------------------------ host side
+# scratch int64 arrays for the rank-2 fast path of the shape functions (one shape tensor is 16
+# bytes); reused across calls, so the binding is not re-entrant across threads
+_SH2 = [(ctypes.c_int64 * 2)() for _ in range(3)]
+
+
 def nimble_dense_shape(x_shape: Sequence[int], w_shape: Sequence[int]) -> Tuple[int, int]:
+    if len(x_shape) == 2 and len(w_shape) == 2:
+        xs, ws, out = _SH2
+        xs[0], xs[1] = x_shape
+        ws[0], ws[1] = w_shape
+        rc = _lib.nimble_dense_shape(xs, 2, ws, 2, out) if _lib is not None else load().nimble_dense_shape(xs, 2, ws, 2, out)
+        if rc != 0:
+            raise NimbleError(rc, last_error())
+        return out[0], out[1]
     out = (ctypes.c_int64 * 2)(-1, -1)
     _check(load().nimble_dense_shape(_arr(x_shape), len(x_shape), _arr(w_shape), len(w_shape), out))
     return int(out[0]), int(out[1])
@@ -132,23 +151,42 @@ dense_shape = nimble_dense_shape
 
 
 def batch_matmul_shape(a_shape, b_shape, trans_b: bool) -> Tuple[int, int, int]:
+    if len(a_shape) == 3 and len(b_shape) == 3:
+        a, b, out = _SH3
+        a[0], a[1], a[2] = a_shape
+        b[0], b[1], b[2] = b_shape
+        _check(load().nimble_batch_matmul_shape(a, 3, b, 3, int(bool(trans_b)), out))
+        return out[0], out[1], out[2]
     out = (ctypes.c_int64 * 3)(-1, -1, -1)
     _check(load().nimble_batch_matmul_shape(_arr(a_shape), len(a_shape), _arr(b_shape), len(b_shape),
                                             int(bool(trans_b)), out))
     return int(out[0]), int(out[1]), int(out[2])
 
 
+_SH2L = [(ctypes.c_int64 * 2)() for _ in range(6)]
+_SH3 = [(ctypes.c_int64 * 3)() for _ in range(3)]
+
+
 def lstm_shape(x_shape, h_shape, c_shape, w_shape):
     for s in (x_shape, h_shape, c_shape, w_shape):
         if len(s) != 2:
             raise NimbleError(-2, "lstm expects rank-2 shapes")
-    ho, co = (ctypes.c_int64 * 2)(-1, -1), (ctypes.c_int64 * 2)(-1, -1)
-    _check(load().nimble_lstm_shape(_arr(x_shape), _arr(h_shape), _arr(c_shape), _arr(w_shape), ho, co))
-    return (int(ho[0]), int(ho[1])), (int(co[0]), int(co[1]))
+    xs, hs, cs, ws, ho, co = _SH2L
+    xs[0], xs[1] = x_shape
+    hs[0], hs[1] = h_shape
+    cs[0], cs[1] = c_shape
+    ws[0], ws[1] = w_shape
+    _check(load().nimble_lstm_shape(xs, hs, cs, ws, ho, co))
+    return (ho[0], ho[1]), (co[0], co[1])
 
 
 def storage_bytes(shape: Sequence[int], dtype: int) -> int:
-    n = int(load().nimble_storage_bytes(_arr(shape), len(shape), dtype))
+    if len(shape) == 2:
+        arr = _SH2[2]
+        arr[0], arr[1] = shape
+        n = load().nimble_storage_bytes(arr, 2, dtype)
+    else:
+        n = int(load().nimble_storage_bytes(_arr(shape), len(shape), dtype))
     if n < 0:
         raise NimbleError(n, last_error())
     return n
@@ -180,6 +218,14 @@ def dense_plan(M: int, N: int, K: int, epilogue: int = EPI_BIAS, out_dtype: int 
     c = _CPlan()
     _check(load().nimble_dense_plan(M, N, K, epilogue, out_dtype, force_variant, ctypes.byref(c)))
     return _plan(c)
+
+
+def dense_table_set(N: int, K: int, epilogue: int, entries: Sequence[Tuple[int, int, int, int]]) -> None:
+    """entries: (m_lo, m_hi, variant, split_k); an empty list removes the table."""
+    arr = (_CTableEntry * max(len(entries), 1))()
+    for i, (lo, hi, v, sk) in enumerate(entries):
+        arr[i] = _CTableEntry(int(lo), int(hi), int(v), int(sk))
+    _check(load().nimble_dense_table_set(N, K, epilogue, arr, len(entries)))
 
 
 def batch_matmul_plan(batch: int, M: int, N: int, K: int, trans_b: bool, out_dtype: int = BF16) -> Plan:

@@ -23,10 +23,10 @@ namespace nimble {
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, bool MEDGE, bool PINGPONG>
+template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, bool PINGPONG>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
                                                uint4* smem) {
-  constexpr int S = 4;
+  static_assert(S >= 4, "the pipeline keeps S-2 stages in flight and needs at least two");
   constexpr int NT = WGM * WGN * 64;
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -261,12 +261,15 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
+// S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit; a
+// launch with fewer tiles than compute units runs one workgroup per unit anyway and is bound
+// by load latency, so it takes the deep ring (8 stages, six in flight) instead.
+template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
 __global__ void __launch_bounds__(WGM* WGN * 64)
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
   // the two-group schedule pays off when a wave's multiply phase is long: 128x64 wave tiles
   constexpr bool kPingPong = (BM / WGM) * (BN / WGN) >= 128 * 64 && WGM * WGN == 8;
-  __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
+  __shared__ __attribute__((aligned(16))) uint4 smem[S * (BM + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -278,11 +281,11 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
       return;
     }
     if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
-      gemm_ring_body<BM, BN, WGM, WGN, true, kPingPong>(g, m0, n0, smem);
+      gemm_ring_body<BM, BN, WGM, WGN, S, true, kPingPong>(g, m0, n0, smem);
       return;
     }
   }
-  gemm_ring_body<BM, BN, WGM, WGN, false, kPingPong>(g, m0, n0, smem);
+  gemm_ring_body<BM, BN, WGM, WGN, S, false, kPingPong>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------

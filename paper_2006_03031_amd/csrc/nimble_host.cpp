@@ -8,6 +8,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <map>
+#include <tuple>
+#include <vector>
 
 namespace nimble {
 
@@ -114,6 +117,17 @@ static bool split_k_ok(int v, int64_t batch, int64_t N, int64_t K, int sk) {
   return per >= 4 && per * (sk - 1) < stages;                      // every slice gets work
 }
 
+// Tuned overrides, keyed by (N, K, epilogue).
+static std::map<std::tuple<int64_t, int64_t, int>, std::vector<nimble_table_entry>> g_tables;
+
+static const nimble_table_entry* table_lookup(int64_t M, int64_t N, int64_t K, int epilogue) {
+  auto it = g_tables.find(std::make_tuple(N, K, epilogue));
+  if (it == g_tables.end()) return nullptr;
+  for (const nimble_table_entry& e : it->second)
+    if (M >= e.m_lo && M <= e.m_hi) return &e;
+  return nullptr;
+}
+
 struct Launch {
   int variant = -1;
   int split_k = 1;
@@ -194,6 +208,13 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
   if (variant == NIMBLE_VAR_AUTO) {
     if (!aligned_k || M == 0 || N == 0) {
       variant = NIMBLE_VAR_GENERIC;
+    } else if (const nimble_table_entry* e = (batch == 1 && opt.use_table) ? table_lookup(M, N, K, epilogue) : nullptr;
+               e && (e->variant == NIMBLE_VAR_SKINNY16 ||
+                     (tiled_variant_ok(e->variant, M, N, K) && split_k_ok(e->variant, 1, N, K, e->split_k) &&
+                      (e->split_k <= 1 ||
+                       (uint64_t)e->split_k * (uint64_t)M * (uint64_t)N * 4u <= opt.max_workspace)))) {
+      variant = e->variant;  // tuned: one launch of this configuration
+      split_k = e->split_k > 1 ? e->split_k : 1;
     } else {
       const Launch single = best_launch(batch, M, N, K, epilogue, opt.max_workspace, true);
       variant = single.variant < 0 ? NIMBLE_VAR_GENERIC : single.variant;
@@ -393,6 +414,33 @@ int nimble_dense_plan(int64_t M, int64_t N, int64_t K, int epilogue, int out_dty
   PlanOptions opt;
   opt.max_workspace = ~0ull;  // report the plan for a caller that provides what it asks for
   return plan_dense(1, M, N, K, epilogue, force_variant, opt, plan);
+}
+
+int nimble_dense_table_set(int64_t N, int64_t K, int epilogue, const nimble_table_entry* entries,
+                           int count) {
+  clear_error();
+  if (N < 0 || K < 0 || count < 0) return fail(NIMBLE_ERR_ARG, "negative argument");
+  if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
+    return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
+  const auto key = std::make_tuple(N, K, epilogue);
+  if (count == 0) {
+    g_tables.erase(key);
+    return NIMBLE_OK;
+  }
+  if (!entries) return fail(NIMBLE_ERR_NULL, "null table");
+  std::vector<nimble_table_entry> t;
+  for (int i = 0; i < count; ++i) {
+    const nimble_table_entry& e = entries[i];
+    if (e.m_lo < 0 || e.m_hi < e.m_lo) return fail(NIMBLE_ERR_ARG, "entry %d: bad M range", i);
+    if (e.variant < NIMBLE_VAR_SKINNY16 || e.variant >= NIMBLE_VAR_COUNT)
+      return fail(NIMBLE_ERR_ARG, "entry %d: variant %d cannot be tabled", i, e.variant);
+    if (e.split_k < 0 || e.split_k > 64) return fail(NIMBLE_ERR_ARG, "entry %d: bad split_k", i);
+    if (e.variant == NIMBLE_VAR_SKINNY16 && e.m_hi > 64)
+      return fail(NIMBLE_ERR_ARG, "entry %d: skinny16 serves M <= 64", i);
+    t.push_back(e);
+  }
+  g_tables[key] = t;
+  return NIMBLE_OK;
 }
 
 int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int trans_b,

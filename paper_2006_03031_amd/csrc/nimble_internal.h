@@ -22,6 +22,7 @@ struct PlanOptions {
   uint64_t max_workspace = 0;   // bytes of caller scratch available (split-K partial sums)
   bool allow_row_split = true;  // may dispatch x = bm*k + r as two launches
   int force_split_k = 0;        // > 0 with a forced variant: cut K into exactly this many slices
+  bool use_table = true;        // consult the tuned dispatch table before the cost model
 };
 
 // Dispatch table shared by dense (batch = 1) and batch_matmul.

@@ -18,7 +18,15 @@ from . import binding as nb
 _TORCH_DTYPE = {nb.BF16: torch.bfloat16, nb.F32: torch.float32}
 
 
+try:  # raw handle of torch's current stream without building a Stream object (several us cheaper)
+    _raw_stream = torch._C._cuda_getCurrentRawStream
+except AttributeError:  # pragma: no cover - older torch
+    _raw_stream = None
+
+
 def _stream() -> int:
+    if _raw_stream is not None:
+        return _raw_stream(torch.cuda.current_device())
     return torch.cuda.current_stream().cuda_stream
 
 

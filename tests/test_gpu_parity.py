@@ -97,6 +97,15 @@ def test_tiled_variants_ragged_N_and_K(rt, nb, variant):
     _sweep(rt, nb, variant, N=bn + 6, K=1024, Ms=Ms, epilogue="bias", out_dtype=1)
 
 
+@pytest.mark.parametrize("variant", [4, 5, 6])
+def test_ring_variants_short_and_odd_stage_counts(rt, nb, variant):
+    # K of 1, 2, 3, 5 and 9 ring stages: the pipeline prologue, the tail waits and the
+    # ping-pong barrier count must hold when there are fewer stages than ring slots
+    bm, bn = TILED[variant]
+    for K in (32, 64, 96, 160, 288):
+        _sweep(rt, nb, variant, N=bn, K=K, Ms=[bm, bm + 5, 2 * bm], epilogue="bias")
+
+
 def test_split_k_forced_and_auto(rt, nb):
     # forced: every ring variant, several slice counts, residues along M, both output types
     for variant, (bm, bn) in ((4, (128, 128)), (5, (256, 128)), (6, (256, 256))):
