@@ -261,9 +261,10 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   }
 }
 
-// S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit; a
-// launch with fewer tiles than compute units runs one workgroup per unit anyway and is bound
-// by load latency, so it takes the deep ring (8 stages, six in flight) instead.
+// S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit.  A
+// deeper ring (8 stages for 128x128, 6 for 256x128) was measured and changed nothing: a lone
+// workgroup is bound by the ~37 bytes per clock one compute unit pulls through the direct
+// global->LDS path, not by the latency of the loads.
 template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
 __global__ void __launch_bounds__(WGM* WGN * 64)
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {

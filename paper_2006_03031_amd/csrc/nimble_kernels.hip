@@ -58,34 +58,22 @@ static int launch_tile(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   return check_hip(hipGetLastError(), "tile kernel launch");
 }
 
-template <int BM, int BN, int WGM, int WGN, int DEEP>
+template <int BM, int BN, int WGM, int WGN>
 static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  int group_m = 4;
+  int group_m = 4;  // measured best of 1..32 on the BERT-large FFN shapes
   if (const char* env = std::getenv("NIMBLE_GROUP_M")) {  // tuning knob: tile rows per L2 group
     const int v = std::atoi(env);
     if (v > 0) group_m = v;
   }
   if (group_m > tiles_m) group_m = tiles_m;
-  const int sk = p.split_k > 1 ? p.split_k : 1;
-  dim3 grid(p.grid[0], sk, p.grid[2]), block(WGM * WGN * 64);
-  // fewer workgroups than compute units: one per unit, latency bound -> the deep ring
-  const bool deep = DEEP > 4 && (long long)p.grid[0] * sk * p.grid[2] <= 256;
-  if (deep) {
-    if (p.residue_copy)
-      hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true, DEEP>), grid, block, 0, st, g, tiles_m,
-                         tiles_n, group_m);
-    else
-      hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false, DEEP>), grid, block, 0, st, g, tiles_m,
-                         tiles_n, group_m);
-  } else {
-    if (p.residue_copy)
-      hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true, 4>), grid, block, 0, st, g, tiles_m,
-                         tiles_n, group_m);
-    else
-      hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false, 4>), grid, block, 0, st, g, tiles_m,
-                         tiles_n, group_m);
-  }
+  dim3 grid(p.grid[0], p.split_k > 1 ? p.split_k : 1, p.grid[2]), block(WGM * WGN * 64);
+  if (p.residue_copy)
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
+  else
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, g, tiles_m,
+                       tiles_n, group_m);
   return check_hip(hipGetLastError(), "ring kernel launch");
 }
 
@@ -125,9 +113,9 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
     }
     case NIMBLE_VAR_T32x128: return launch_tile<32, 128, 1, 4>(g, p, st);
     case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
-    case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2, 8>(g, p, st);
-    case NIMBLE_VAR_T256x128: return launch_ring<256, 128, 4, 2, 6>(g, p, st);
-    case NIMBLE_VAR_T256x256: return launch_ring<256, 256, 2, 4, 4>(g, p, st);
+    case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T256x128: return launch_ring<256, 128, 4, 2>(g, p, st);
+    case NIMBLE_VAR_T256x256: return launch_ring<256, 256, 2, 4>(g, p, st);
     default: return fail(NIMBLE_ERR_ARG, "unknown variant %d", p.variant);
   }
 }
