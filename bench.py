@@ -174,6 +174,32 @@ def small_m_probe():
         us_g = s.elapsed_time(e) * 1e3 / (4 * 128)
         out[f"lstm_step_B{B}_warm"] = {"us_per_step": round(us, 2), "us_per_step_graph": round(us_g, 2),
                                        "eff_GBps_graph": round(nbytes / us_g / 1e3, 1)}
+    # the same token loop as bytecode on the interpreter: shape_of, shape function, allocation from
+    # the pool and invoke per token (about two dozen coarse instructions), host cost per token split
+    # into kernel dispatch+launch and everything else
+    from paper_2006_03031_amd import vm
+    exe = vm.Executable.from_assembler(vm.lstm_sequence_program(), [dw, db])
+    pool = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    for B in (1, 64):
+        xs = torch.empty((128, B, 512), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        h0 = torch.zeros((B, 512), dtype=torch.bfloat16, device="cuda")
+        c0 = torch.zeros((B, 512), dtype=torch.float32, device="cuda")
+        exe.run([xs, h0, c0], pool)
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(4):
+            exe.run([xs, h0, c0], pool)
+        e.record()
+        torch.cuda.synchronize()
+        prof = exe.profile()
+        launch_ns = prof["packed"]["lstm_gates"][1]
+        out[f"vm_lstm_B{B}"] = {"us_per_step": round(s.elapsed_time(e) * 1e3 / (4 * 128), 2),
+                                "instructions_per_step": round(prof["instructions"] / 128, 1),
+                                "host_us_per_step_launch": round(launch_ns / 128e3, 2),
+                                "host_us_per_step_others": round((prof["host_ns"] - launch_ns) / 128e3, 2),
+                                "pool_high_water_bytes": prof["pool_high_water"]}
+    del pool
     # attention, 12 heads x 64, one launch versus the three-call chain
     for L in (128, 512):
         q = torch.empty((12, L, 64), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)

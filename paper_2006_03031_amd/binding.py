@@ -9,7 +9,7 @@ from typing import Optional, Sequence, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libnimble_hip.so")
-_HEADER = os.path.join(os.path.dirname(_PKG), "include", "nimble.h")
+_HEADERS = [os.path.join(os.path.dirname(_PKG), "include", h) for h in ("nimble.h", "nimble_vm.h")]
 
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU_ERF = 0, 1, 2
 BF16, F32 = 0, 1
@@ -108,10 +108,12 @@ def load():
 
 
 def exported_symbols() -> Sequence[str]:
-    """Names of the functions ``include/nimble.h`` declares."""
-    text = open(_HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(nimble_[a-z0-9_]+)\s*\(", text)))
+    """Names of the functions the headers under ``include/`` declare."""
+    names = set()
+    for header in _HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names.update(re.findall(r"\b(nimble_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def last_error() -> str:

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libnimble_hip.so")
-SOURCES = ["nimble_host.cpp", "nimble_kernels.hip"]  # the .h files under csrc/ hold the kernels
+SOURCES = ["nimble_host.cpp", "nimble_vm.cpp", "nimble_kernels.hip"]  # the .h files under csrc/ hold the kernels
 
 
 def hipcc_command(out: str = LIB):
@@ -37,7 +37,7 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "nimble.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "nimble.h"), os.path.join(ROOT, "include", "nimble_vm.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
