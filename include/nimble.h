@@ -83,11 +83,16 @@ typedef enum nimble_variant {
 /* A forced variant may also force the K split: force_variant = variant | NIMBLE_FORCE_SPLIT_K(n)
  * cuts K into n slices (ring variants only; needs n*M*N*4 bytes of workspace). */
 #define NIMBLE_FORCE_SPLIT_K(n) (((n) & 0xff) << 8)
+/* ... and the tile height: the 256 x 256 variant is also built with tiles of 128, 160, 192 and
+ * 224 rows (N a multiple of 256, K of 32).  With the run-time M known the dispatch function picks
+ * the height at which the tile rows fill whole rounds of the 256 compute units, instead of
+ * paying a mostly empty last round: the residue handling of Section 3.5 applied one level up. */
+#define NIMBLE_FORCE_TILE_ROWS(rows) ((((rows) / 16) & 0xff) << 16)
 
 /* What the dispatch function decided for one run-time shape (host only). */
 typedef struct nimble_plan {
   int32_t variant;        /* nimble_variant                                       */
-  int32_t bm, bn, bk;     /* macro tile of the variant                            */
+  int32_t bm, bn, bk;     /* macro tile of the launch (bm may be a reduced height)  */
   int64_t k;              /* floor(M / bm): number of full tiles along M          */
   int32_t r;              /* M mod bm: the residue the kernel copy is chosen by   */
   int32_t residue_copy;   /* 1 when the r != 0 copy (or an N/K edge) is launched  */

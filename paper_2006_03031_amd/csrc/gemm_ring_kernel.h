@@ -23,7 +23,9 @@ namespace nimble {
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, bool PINGPONG>
+enum { RING_DOUBLE = 0, RING_PINGPONG = 1 };
+
+template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
                                                uint4* smem) {
   static_assert(S >= 4, "the pipeline keeps S-2 stages in flight and needs at least two");
@@ -31,13 +33,20 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 16, TN = WN / 16;
-  constexpr int A_LD = BM * 4 / NT, B_LD = BN * 4 / NT;
+  // one pass of the workgroup's loads covers PASS rows; a tile height that is not a whole number
+  // of passes rounds up: the ring holds BMP rows of A per stage and the extra rows are loaded
+  // from the tile's last row (in bounds, never read back), so that every wave issues the same
+  // number of loads per stage and one wait count serves them all
+  constexpr int PASS = NT / 4;
+  constexpr int A_LD = (BM + PASS - 1) / PASS, B_LD = BN / PASS;
+  constexpr int BMP = A_LD * PASS;
   constexpr int LD = A_LD + B_LD;
-  static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the workgroup");
+  static_assert(BN % PASS == 0 && B_LD >= 1, "tile too narrow for the workgroup");
+  static_assert(WM % 16 == 0 && WM >= 16, "a wave owns whole 16-row MFMA tiles");
   static_assert(WN == 64, "the LDS epilogue assumes 64 output columns per wave");
-  static_assert(NW * WM * WN * 2 <= S * (BM + BN) * 64, "epilogue staging does not fit in the ring");
-  uint4(*As)[BM * 4] = reinterpret_cast<uint4(*)[BM * 4]>(smem);
-  uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BM * 4);
+  static_assert(NW * WM * WN * 2 <= S * (BMP + BN) * 64, "epilogue staging does not fit in the ring");
+  uint4(*As)[BMP * 4] = reinterpret_cast<uint4(*)[BMP * 4]>(smem);
+  uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BMP * 4);
 
   // gridDim.y > 1: K is cut into gridDim.y slices of whole stages; slice blockIdx.y writes its
   // f32 partial sums to its own [M,N] plane of the output (g.c is then the split-K workspace)
@@ -60,21 +69,22 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   uint32_t a_off[A_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
-    int row = ld_row + i * (NT / 4);
+    int row = ld_row + i * PASS;
+    if (BM % PASS != 0) row = row < BM ? row : BM - 1;
     if (MEDGE) row = (m0 + row < g.M) ? row : (g.M - 1 - m0);
     a_off[i] = (uint32_t)(row * g.lda + ld_c * 8) * 2u;
   }
   const uint32_t b_off = (uint32_t)(ld_row * g.ldb + ld_c * 8) * 2u;
   const u16* a_base = A + (long long)m0 * g.lda;
   const u16* b_base = B + (long long)n0 * g.ldb;
-  const long long b_pass = (long long)(NT / 4) * g.ldb;
+  const long long b_pass = (long long)PASS * g.ldb;
   const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&As[0][wave * 64]));
   const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&Bs[0][wave * 64]));
   auto dma = [&](int ks, int slot) {
     const int k0 = ks << 5;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BM * 64) + i * NT * 16);
+      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BMP * 64) + i * NT * 16);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
       dma16_so(b_off, b_base + i * b_pass + k0, b_dst + slot * (BN * 64) + i * NT * 16);
@@ -103,7 +113,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  if constexpr (PINGPONG) {
+  if constexpr (MODE == RING_PINGPONG) {
     // Waves w and w + NW/2 share a SIMD.  The workgroup runs in two groups half a step out of
     // phase: while group P multiplies stage s, group Q issues its loads and reads its fragments
     // of stage s, then they swap.  A wave never has memory instructions and MFMAs queued
@@ -264,13 +274,20 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 // S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit.  A
 // deeper ring (8 stages for 128x128, 6 for 256x128) was measured and changed nothing: a lone
 // workgroup is bound by the ~37 bytes per clock one compute unit pulls through the direct
-// global->LDS path, not by the latency of the loads.
+// global->LDS path, not by the latency of the loads.  Two 4-wave workgroups of a 256x128 tile
+// per compute unit (3-stage rings, one register set) were measured too: same steady-state rate as
+// the 8-wave ping-pong, slower at whole rounds, so that shape is not built.
+// BM may be any multiple of 16 * WGM: the 256-wide tile is built at 128..256 rows so that the
+// dispatch function can pick the height at which the run-time M fills whole rounds of the chip.
 template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
-__global__ void __launch_bounds__(WGM* WGN * 64)
+__global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
-  // the two-group schedule pays off when a wave's multiply phase is long: 128x64 wave tiles
-  constexpr bool kPingPong = (BM / WGM) * (BN / WGN) >= 128 * 64 && WGM * WGN == 8;
-  __shared__ __attribute__((aligned(16))) uint4 smem[S * (BM + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles
+  // the two-group schedule pays off when a wave's multiply phase is long: the 2 x 4 wave grid
+  // of the 256-wide tiles (wave tiles of 64..128 rows by 64 columns)
+  constexpr int kPingPong = WGM == 2 && WGN == 4 ? RING_PINGPONG : RING_DOUBLE;
+  constexpr int kPass = WGM * WGN * 16;  // rows per load pass: the ring holds whole passes of A
+  constexpr int kBmp = (BM + kPass - 1) / kPass * kPass;
+  __shared__ __attribute__((aligned(16))) uint4 smem[S * (kBmp + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -278,7 +295,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
     // the packed epilogue needs 16-byte aligned output rows; K must be whole 32-wide stages
     const bool ragged = (n0 + BN > g.N) || ((g.K & 31) != 0) || ((g.ldc & 7) != 0);
     if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
-      gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      // (the reduced tile heights are only dispatched to shapes without ragged N or K)
+      if constexpr (BM % 128 == 0) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
       return;
     }
     if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores

@@ -47,7 +47,7 @@ static const int64_t kCUs = 256;
 // the epilogue, which is larger with GELU), divided by how well the variant
 // keeps the matrix cores busy in steady state (measured per variant at
 // M = 8192 on the BERT-large FFN shapes).
-static double tile_cost(int variant, int64_t K, int epilogue) {
+static double tile_cost(int variant, int64_t K, int epilogue, int bm = 0) {
   double eff;
   switch (variant) {
     case NIMBLE_VAR_T32x128: eff = 0.30; break;
@@ -58,7 +58,23 @@ static double tile_cost(int variant, int64_t K, int epilogue) {
     default: return 1e30;
   }
   const double k0 = (epilogue == NIMBLE_EPI_BIAS_GELU_ERF) ? 256.0 : 128.0;
-  return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) / eff;
+  // a tile of another height loads the same weight panel for fewer or more rows: measured
+  // time(bm) / time(256) = 0.28 + 0.72 bm/256 for the 256-wide tile (bm = 128..320)
+  const double height = (bm > 0 && bm != kVariants[variant].bm)
+                            ? 0.28 + 0.72 * (double)bm / (double)kVariants[variant].bm : 1.0;
+  return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) * height / eff;
+}
+
+// Heights the 256-wide tile is built at: 2 wave rows of 4..10 MFMA tiles of 16 rows.
+static const int kTileRows256[] = {320, 288, 256, 224, 192, 160, 128};
+
+bool tile_rows_ok(int variant, int bm, int64_t N, int64_t K) {
+  if (bm == 0 || bm == kVariants[variant].bm) return true;
+  if (variant != NIMBLE_VAR_T256x256) return false;
+  if (N % 256 != 0 || K % 32 != 0) return false;  // the reduced heights have no ragged N/K body
+  for (int h : kTileRows256)
+    if (h == bm) return true;
+  return false;
 }
 
 bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K) {
@@ -84,15 +100,15 @@ static const double kLaunchGapUs = 4.0;
 // matrix cores less efficiently.  Cutting K multiplies the tiles and shortens each; the
 // partial sums then cross HBM once more and a second small kernel adds them up.
 static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
-                            int sk = 1) {
+                            int sk = 1, int bm = 0) {
   const VariantInfo& vi = kVariants[v];
-  const int64_t tiles = batch * ceil_div(rows, vi.bm) * ceil_div(N, vi.bn) * sk;
+  const int64_t tiles = batch * ceil_div(rows, bm > 0 ? bm : vi.bm) * ceil_div(N, vi.bn) * sk;
   const int64_t k_slice = ceil_div(ceil_div(K, 32), sk) * 32;
   // one K step of a tile cannot go faster than the latency of its loads: about 1.8 us per
   // 64-wide step in the register-staged small-tile kernels, 0.3 us per 32-wide ring stage
   const double latency_floor = (v <= NIMBLE_VAR_T64x128) ? (double)ceil_div(k_slice, 64) * 1.8
                                                          : (double)ceil_div(k_slice, 32) * 0.3;
-  double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue) * kUsPerUnit;
+  double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
   if (t_full < latency_floor) t_full = latency_floor;
   const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
   double us = (double)full_rounds * t_full;
@@ -131,6 +147,7 @@ static const nimble_table_entry* table_lookup(int64_t M, int64_t N, int64_t K, i
 struct Launch {
   int variant = -1;
   int split_k = 1;
+  int bm = 0;  // tile height when it differs from the variant's own
   double us = 0;
 };
 
@@ -154,16 +171,32 @@ static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int
       if (best.variant < 0 || us < best.us) {
         best.variant = v;
         best.split_k = sk;
+        best.bm = 0;
         best.us = us;
       }
     }
+    // the same tile at a reduced height: with the run-time M known, pick the height at which
+    // the tile rows fill whole rounds of the chip instead of leaving a mostly empty last round
+    static const bool heights_on = !(std::getenv("NIMBLE_TILE_ROWS") && std::atoi(std::getenv("NIMBLE_TILE_ROWS")) == 0);
+    if (v == NIMBLE_VAR_T256x256 && batch == 1 && heights_on)
+      for (int bm : kTileRows256) {
+        if (bm == kVariants[v].bm || rows <= bm || !tile_rows_ok(v, bm, N, K)) continue;
+        const double us = tiled_cost_us(v, batch, rows, N, K, epilogue, 1, bm);
+        if (us < best.us) {
+          best.variant = v;
+          best.split_k = 1;
+          best.bm = bm;
+          best.us = us;
+        }
+      }
   }
   return best;
 }
 
 static void fill_tiled(nimble_plan* p, int variant, int split_k, int64_t batch, int64_t M, int64_t N,
-                       int64_t K) {
-  const VariantInfo& v = kVariants[variant];
+                       int64_t K, int bm = 0) {
+  VariantInfo v = kVariants[variant];
+  if (bm > 0) v.bm = bm;
   p->variant = variant;
   p->bm = v.bm;
   p->bn = v.bn;
@@ -192,10 +225,13 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     const char* env = std::getenv("NIMBLE_FORCE_VARIANT");
     if (env && *env) variant = std::atoi(env);
   }
-  // a forced variant may carry a forced K split in bits 8..15 (NIMBLE_FORCE_SPLIT_K)
+  // a forced variant may carry a forced K split in bits 8..15 (NIMBLE_FORCE_SPLIT_K) and a
+  // forced tile height in bits 16..23 (NIMBLE_FORCE_TILE_ROWS)
   int forced_sk = opt.force_split_k;
+  int tile_rows = 0;
   if (variant >= 0) {
     if ((variant >> 8) & 0xff) forced_sk = (variant >> 8) & 0xff;
+    tile_rows = ((variant >> 16) & 0xff) * 16;
     variant &= 0xff;
   }
   if (variant < NIMBLE_VAR_AUTO || variant >= NIMBLE_VAR_COUNT)
@@ -219,6 +255,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
       const Launch single = best_launch(batch, M, N, K, epilogue, opt.max_workspace, true);
       variant = single.variant < 0 ? NIMBLE_VAR_GENERIC : single.variant;
       split_k = single.split_k;
+      tile_rows = single.bm;
       // Alternative: two launches.  Whole tile rows (all k of them, or as many as fill whole
       // rounds of the chip) run the r = 0 copy of a big-tile variant: no bounds code, no
       // partial round.  The remaining rows, residue included, run whatever suits their
@@ -244,6 +281,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
               best_us = us;
               variant = v;
               split_k = 1;
+              tile_rows = 0;
               split_rows = head;
               residue_variant = tail.variant;
             }
@@ -289,6 +327,11 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
   }
   if (!tiled_variant_ok(variant, M, N, K))
     return fail(NIMBLE_ERR_ARG, "variant %s cannot run K=%lld", kVariants[variant].name, (long long)K);
+  if (!tile_rows_ok(variant, tile_rows, N, K))
+    return fail(NIMBLE_ERR_ARG, "variant %s is not built with tiles of %d rows for N=%lld K=%lld",
+                kVariants[variant].name, tile_rows, (long long)N, (long long)K);
+  if (tile_rows > 0 && tile_rows != kVariants[variant].bm && forced_sk > 1)
+    return fail(NIMBLE_ERR_ARG, "a reduced tile height cannot be combined with a K split");
   if (force_variant != NIMBLE_VAR_AUTO && forced_sk > 0) {
     if (!split_k_ok(variant, batch, N, K, forced_sk))
       return fail(NIMBLE_ERR_ARG, "variant %s cannot cut K=%lld into %d slices", kVariants[variant].name,
@@ -298,7 +341,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
                   (unsigned long long)((uint64_t)forced_sk * (uint64_t)M * (uint64_t)N * 4u));
     split_k = forced_sk;
   }
-  fill_tiled(p, variant, split_k, batch, split_rows > 0 ? split_rows : M, N, K);
+  fill_tiled(p, variant, split_k, batch, split_rows > 0 ? split_rows : M, N, K, tile_rows);
   if (split_rows > 0) {
     // k and r describe the whole call; grid and residue_copy describe the first launch
     p->k = M / p->bm;

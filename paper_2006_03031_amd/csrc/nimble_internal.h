@@ -17,6 +17,8 @@ int fail(int code, const char* fmt, ...);
 void clear_error();
 
 bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
+// bm = 0 or the variant's own height: always; else the heights the variant is also built at.
+bool tile_rows_ok(int variant, int bm, int64_t N, int64_t K);
 
 struct PlanOptions {
   uint64_t max_workspace = 0;   // bytes of caller scratch available (split-K partial sums)

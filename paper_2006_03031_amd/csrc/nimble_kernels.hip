@@ -58,7 +58,7 @@ static int launch_tile(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   return check_hip(hipGetLastError(), "tile kernel launch");
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int S = 4>
 static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   int group_m = 4;  // measured best of 1..32 on the BERT-large FFN shapes
@@ -69,10 +69,10 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   if (group_m > tiles_m) group_m = tiles_m;
   dim3 grid(p.grid[0], p.split_k > 1 ? p.split_k : 1, p.grid[2]), block(WGM * WGN * 64);
   if (p.residue_copy)
-    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true, S>), grid, block, 0, st, g, tiles_m,
                        tiles_n, group_m);
   else
-    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, g, tiles_m,
+    hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false, S>), grid, block, 0, st, g, tiles_m,
                        tiles_n, group_m);
   return check_hip(hipGetLastError(), "ring kernel launch");
 }
@@ -115,7 +115,17 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
     case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T256x128: return launch_ring<256, 128, 4, 2>(g, p, st);
-    case NIMBLE_VAR_T256x256: return launch_ring<256, 256, 2, 4>(g, p, st);
+    case NIMBLE_VAR_T256x256:
+      switch (p.bm) {  // the tile height the dispatch function chose for this M
+        case 320: return launch_ring<320, 256, 2, 4>(g, p, st);
+        case 288: return launch_ring<288, 256, 2, 4>(g, p, st);
+        case 256: return launch_ring<256, 256, 2, 4>(g, p, st);
+        case 224: return launch_ring<224, 256, 2, 4>(g, p, st);
+        case 192: return launch_ring<192, 256, 2, 4>(g, p, st);
+        case 160: return launch_ring<160, 256, 2, 4>(g, p, st);
+        case 128: return launch_ring<128, 256, 2, 4>(g, p, st);
+        default: return fail(NIMBLE_ERR_ARG, "t256x256 is not built with tiles of %d rows", p.bm);
+      }
     default: return fail(NIMBLE_ERR_ARG, "unknown variant %d", p.variant);
   }
 }

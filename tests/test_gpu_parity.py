@@ -97,6 +97,36 @@ def test_tiled_variants_ragged_N_and_K(rt, nb, variant):
     _sweep(rt, nb, variant, N=bn + 6, K=1024, Ms=Ms, epilogue="bias", out_dtype=1)
 
 
+@pytest.mark.parametrize("rows", [128, 160, 192, 224, 288, 320])
+def test_tile_heights_of_the_256_wide_variant_every_residue(rt, nb, rows):
+    # the 256 x 256 variant at its other tile heights: every residue M mod rows, k = 0, 1, 2,
+    # heights that are not a whole number of load passes (160, 192, 224, 288, 320 vs passes of 128)
+    forced = 6 | ((rows // 16) << 16)
+    p = nb.dense_plan(rows + 1, 512, 128, force_variant=forced)
+    assert (p.variant, p.bm, p.k, p.r, p.residue_copy) == (6, rows, 1, 1, 1)
+    _sweep(rt, nb, forced, N=512, K=128, Ms=range(1, 2 * rows + 2))
+    for K in (32, 96, 160, 1024):   # fewer stages than ring slots, odd counts, a long K
+        _sweep(rt, nb, forced, N=256, K=K, Ms=[rows, rows + 5, 3 * rows - 1], epilogue="bias", out_dtype=1)
+
+
+def test_auto_dispatch_picks_a_tile_height_that_fills_the_rounds(rt, nb):
+    # BERT-large FFN2 just past 8192 rows: one round of 160-row tiles instead of two rounds
+    p = nb.dense_plan(8300, 1024, 4096)
+    assert p.variant == 6 and p.bm in (128, 160, 192) and p.grid[0] <= 256 and p.split_rows == 0
+    # FFN1 just past two rounds of 256-row tiles: taller tiles keep it at two rounds
+    p = nb.dense_plan(8300, 4096, 1024, nb.EPI_BIAS_GELU_ERF)
+    if p.split_rows == 0:
+        assert p.variant == 6 and p.bm in (288, 320) and p.grid[0] <= 512
+    to_dev, _, from_dev, _ = _dev()
+    for (M, N, K, epi) in [(8300, 1024, 4096, "bias"), (2100, 4096, 1024, "bias_gelu")]:
+        rng = np.random.default_rng([5, M])
+        x, w, b = wl.uniform_bf16(rng, (M, K)), wl.normal_bf16(rng, (N, K)), wl.uniform_bf16(rng, (N,))
+        y = rt.dense(to_dev(x), to_dev(w), to_dev(b), EPI[epi])
+        rows = np.r_[0:3, M // 2:M // 2 + 3, M - 260:M]   # sampled rows, the last tile row included
+        ref = oracle.dense(x.f32[rows], w.f32, b.f32, epi)
+        assert _err(from_dev(y)[rows], ref) <= TOL, (M, N, K)
+
+
 @pytest.mark.parametrize("variant", [4, 5, 6])
 def test_ring_variants_short_and_odd_stage_counts(rt, nb, variant):
     # K of 1, 2, 3, 5 and 9 ring stages: the pipeline prologue, the tail waits and the

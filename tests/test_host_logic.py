@@ -137,13 +137,13 @@ def test_auto_dispatch_table():
     # one row past a tile boundary: either the r != 0 copy, or the split dispatch
     # (k full tiles through the r = 0 copy, the residue rows through a small-M kernel)
     p = nb.dense_plan(8193, 4096, 1024)
-    assert p.k * p.bm + p.r == 8193 and p.r == 1
+    assert p.k * p.bm + p.r == 8193 and p.r == 8193 % p.bm
     if p.split_rows:
         assert p.split_rows == p.k * p.bm and p.residue_copy == 0
         assert nb.variant_name(p.residue_variant) == "skinny16"
         assert p.grid[0] == (p.split_rows // p.bm) * (4096 // p.bn)
     else:
-        assert p.residue_copy == 1
+        assert p.residue_copy == 1 and p.grid[0] == (p.k + 1) * (4096 // p.bn)
     assert nb.dense_plan(100, 128, 100).name == "generic"
     assert nb.dense_plan(100, 128, 0).name == "generic"
     for M in range(65, 1200, 7):
@@ -163,6 +163,38 @@ def test_auto_dispatch_table():
                     assert nb.variant_name(p.residue_variant) == "skinny16"
             forced = nb.dense_plan(M, N, K, force_variant=p.variant)
             assert forced.split_rows == 0  # a forced variant is one launch
+
+
+def test_forced_tile_height_plans():
+    # the 256-wide variant at its other heights: same residue identity, grid from the chosen height
+    for rows in (128, 160, 192, 224, 256, 288, 320):
+        forced = 6 | ((rows // 16) << 16)
+        for M in list(range(1, 2 * rows + 2, 7)) + [8192, 8193, 10000]:
+            p = nb.dense_plan(M, 4096, 1024, force_variant=forced)
+            assert (p.variant, p.bm, p.bn) == (6, rows, 256)
+            assert (p.k, p.r) == oracle.residue_split(M, rows)
+            assert p.grid[0] == -(-M // rows) * 16 and p.split_rows == 0 and p.split_k == 1
+            assert p.residue_copy == int(p.r != 0)
+    for bad in (6 | (9 << 16), 6 | (21 << 16), 5 | (12 << 16), 4 | (6 << 16)):  # 144, 336 rows; other variants
+        with pytest.raises(nb.NimbleError) as e:
+            nb.dense_plan(1000, 4096, 1024, force_variant=bad)
+        assert e.value.code == -8
+    with pytest.raises(nb.NimbleError):   # no ragged N for the other heights
+        nb.dense_plan(1000, 4096 + 128, 1024, force_variant=6 | (12 << 16))
+    with pytest.raises(nb.NimbleError):   # nor ragged K
+        nb.dense_plan(1000, 4096, 1024 + 8, force_variant=6 | (12 << 16))
+    with pytest.raises(nb.NimbleError):   # nor together with a K split
+        nb.dense_plan(1000, 4096, 1024, force_variant=6 | (12 << 16) | (2 << 8))
+    # automatic choice: the tile rows of the chosen height fit the rounds a taller or shorter
+    # 256-row tiling would have wasted
+    for M in range(5700, 10700, 61):
+        for (N, K) in ((4096, 1024), (1024, 4096)):
+            p = nb.dense_plan(M, N, K)
+            if p.variant == 6 and p.bm != 256:
+                assert p.split_rows == 0 and N % 256 == 0 and K % 32 == 0
+                assert p.grid[0] == -(-M // p.bm) * (N // 256)
+                rounds = -(-p.grid[0] // 256)
+                assert -(-(-(-M // 256) * (N // 256)) // 256) >= rounds or p.bm < 256
 
 
 def test_plan_rejects_bad_arguments():
