@@ -72,6 +72,13 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n" ::"v"(g), "s"(lds_addr)
                : "memory", "m0");
 }
+// acc += a . b on the matrix core with the accumulator held in place in the accumulation
+// registers.  Written as a volatile statement: the order in the source is the order issued, and
+// the register allocator cannot decide to shuffle accumulators between register files.
+__device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 // Same, addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit per-lane
 // byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
 __device__ __forceinline__ void dma16_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {

@@ -2,6 +2,8 @@
 // split-K reduction.
 #ifndef NIMBLE_GEMM_RING_KERNEL_H_
 #define NIMBLE_GEMM_RING_KERNEL_H_
+#include <type_traits>
+
 #include "device_common.h"
 #include "gemm_tile_kernel.h"
 
@@ -23,12 +25,12 @@ namespace nimble {
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-enum { RING_DOUBLE = 0, RING_PINGPONG = 1 };
+enum { RING_DOUBLE = 0, RING_PINGPONG = 1, RING_SOLO = 2 };
 
 template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
                                                uint4* smem) {
-  static_assert(S >= 4, "the pipeline keeps S-2 stages in flight and needs at least two");
+  static_assert(S >= 4 || (MODE == RING_SOLO && S == 3), "the pipeline keeps S-2 stages in flight");
   constexpr int NT = WGM * WGN * 64;
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -43,7 +45,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   constexpr int LD = A_LD + B_LD;
   static_assert(BN % PASS == 0 && B_LD >= 1, "tile too narrow for the workgroup");
   static_assert(WM % 16 == 0 && WM >= 16, "a wave owns whole 16-row MFMA tiles");
-  static_assert(WN == 64, "the LDS epilogue assumes 64 output columns per wave");
+  static_assert(WN % 64 == 0, "the LDS epilogue stages 64-column blocks");
   static_assert(NW * WM * WN * 2 <= S * (BMP + BN) * 64, "epilogue staging does not fit in the ring");
   uint4(*As)[BMP * 4] = reinterpret_cast<uint4(*)[BMP * 4]>(smem);
   uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BMP * 4);
@@ -104,10 +106,14 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s)
-    if (s < KS) dma(s, s);
+  for (int s = 0; s < S - 1; ++s) {
+    if constexpr (MODE == RING_SOLO)
+      dma(s < KS ? s : KS - 1, s);  // always S-1 stages in flight (see the stage code below)
+    else if (s < KS)
+      dma(s, s);
+  }
 
-  if (KS - 1 >= S - 2)
+  if (MODE == RING_SOLO || KS - 1 >= S - 2)
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
   else
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -167,6 +173,58 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       }
     }
     if (!is_q) __syncthreads();
+  } else if constexpr (MODE == RING_SOLO) {
+    // One wave per SIMD, so nothing else hides this wave's LDS latency: the fragments of stage
+    // s+1 are read into the second register set in between the MFMAs of stage s, and the steady
+    // state is straight-line code (no branch inside a stage), so that the compiler's wait-count
+    // insertion can see that the MFMAs of stage s depend only on reads that completed before the
+    // barrier and lets them start at once.
+    bf16x8 xa[2][TM], wb[2][TN];
+    const uint4* a_rd = &As[0][fr_a];
+    const uint4* b_rd = &Bs[0][fr_b];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(a_rd[j * 64]);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(b_rd[i * 64]);
+    // Every stage runs the same code, also the last S-1 of a tile: past the end of K the loads
+    // fetch the last stage again (in bounds, into a slot nobody reads any more) and the
+    // fragment reads fetch stale data that is never multiplied.  That keeps the count of loads
+    // in flight the same at every stage, so one wait count serves them all.
+    auto stage = [&](const int ks, auto cur_tag) {
+      constexpr int CUR = decltype(cur_tag)::value;
+      // stage ks+1 has landed once only the S-3 younger stages are in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
+      __syncthreads();
+      const int ld = ks + S - 1;
+      dma(ld < KS ? ld : KS - 1, ld % S);  // into the slot of stage ks-1, read before this barrier
+      const int nslot = (ks + 1) % S;
+      const uint4* a_nx = a_rd + nslot * (BMP * 4);
+      const uint4* b_nx = b_rd + nslot * (BN * 4);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+        // the two reads stay in front of this weight tile's MFMAs: the empty statement below
+        // is a compiler barrier for memory operations, and the MFMAs are volatile statements
+        wb[CUR ^ 1][i] = as_bf16x8(b_nx[i * 64]);
+#pragma unroll
+        for (int x = i * TM / TN; x < (i + 1) * TM / TN; ++x)  // this tile's share of the TM reads
+          xa[CUR ^ 1][x] = as_bf16x8(a_nx[x * 64]);
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < TM; ++j) mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+      }
+    };
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
+    int ks = 0;
+    for (; ks + 1 < KS; ks += 2) {
+      stage(ks, T0{});
+      stage(ks + 1, T1{});
+    }
+    if (ks < KS) stage(ks, T0{});  // odd number of stages
+    // loads past the end of K may still be in flight into the ring the epilogue is about to reuse;
+    // the MFMAs above are opaque to the compiler's hazard handling: let the last results land
+    // before anything reads the accumulators
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
   } else {
     bf16x8 xa[2][TM], wb[2][TN];
 #pragma unroll
@@ -240,35 +298,38 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     }
     return;
   }
-  // bf16: every wave stages its [WM][64] block in LDS (rows of 128 bytes, chunk c of
-  // row r at slot c ^ ((r >> 1) & 7)) and writes it back out as full 128-byte lines
+  // bf16: every wave stages its [WM][WN] block in LDS as WN/64 blocks of [WM][64] (rows of 128
+  // bytes, chunk c of row r at slot c ^ ((r >> 1) & 7)) and writes it back out as full 128-byte lines
   __syncthreads();  // all fragment reads of the ring are done
+  constexpr int NH = WN / 64;
   unsigned char* region = (unsigned char*)smem + wave * (WM * WN * 2);
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
     const int row = j * 16 + fr_row;
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
-      const int col = i * 16 + fr_q * 4;
+      const int col = (i & 3) * 16 + fr_q * 4;
       const int chunk = (col >> 3) ^ ((row >> 1) & 7);
       uint2 pk;
       pk.x = pack_bf16x2(epilogue(acc[i][j][0], alpha, bias4[i][0], epi),
                          epilogue(acc[i][j][1], alpha, bias4[i][1], epi));
       pk.y = pack_bf16x2(epilogue(acc[i][j][2], alpha, bias4[i][2], epi),
                          epilogue(acc[i][j][3], alpha, bias4[i][3], epi));
-      *(uint2*)(region + row * 128 + chunk * 16 + (col & 4) * 2) = pk;
+      *(uint2*)(region + (i >> 2) * (WM * 128) + row * 128 + chunk * 16 + (col & 4) * 2) = pk;
     }
   }
   // the region is private to the wave: no workgroup barrier, the compiler orders the LDS accesses
   u16* C = (u16*)g.c + (long long)z * g.sc;
 #pragma unroll
-  for (int p = 0; p < WM / 8; ++p) {
-    const int row = p * 8 + (lane >> 3);
-    const int c = lane & 7;
-    const uint4 v = *(const uint4*)(region + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
-    if (MEDGE && m0 + wm * WM + row >= g.M) continue;
-    *(uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + c * 8) = v;
-  }
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int p = 0; p < WM / 8; ++p) {
+      const int row = p * 8 + (lane >> 3);
+      const int c = lane & 7;
+      const uint4 v = *(const uint4*)(region + h * (WM * 128) + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
+      if (MEDGE && m0 + wm * WM + row >= g.M) continue;
+      *(uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + h * 64 + c * 8) = v;
+    }
 }
 
 // S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit.  A
@@ -282,9 +343,10 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
 __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
-  // the two-group schedule pays off when a wave's multiply phase is long: the 2 x 4 wave grid
-  // of the 256-wide tiles (wave tiles of 64..128 rows by 64 columns)
-  constexpr int kPingPong = WGM == 2 && WGN == 4 ? RING_PINGPONG : RING_DOUBLE;
+  // the 2 x 4 wave grid of the 256-wide tiles (wave tiles of 64..160 rows by 64 columns): the
+  // straight-line schedule with two fragment sets while accumulators and both sets fit in a
+  // wave's 256 registers (up to 128 rows per wave), the two-group ping-pong with one set above
+  constexpr int kPingPong = WGM == 2 && WGN == 4 ? (BM <= 256 ? RING_SOLO : RING_PINGPONG) : RING_DOUBLE;
   constexpr int kPass = WGM * WGN * 16;  // rows per load pass: the ring holds whole passes of A
   constexpr int kBmp = (BM + kPass - 1) / kPass * kPass;
   __shared__ __attribute__((aligned(16))) uint4 smem[S * (kBmp + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles

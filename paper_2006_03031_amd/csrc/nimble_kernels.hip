@@ -114,7 +114,8 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
     case NIMBLE_VAR_T32x128: return launch_tile<32, 128, 1, 4>(g, p, st);
     case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
-    case NIMBLE_VAR_T256x128: return launch_ring<256, 128, 4, 2>(g, p, st);
+    case NIMBLE_VAR_T256x128:
+      return launch_ring<256, 128, 4, 2>(g, p, st);
     case NIMBLE_VAR_T256x256:
       switch (p.bm) {  // the tile height the dispatch function chose for this M
         case 320: return launch_ring<320, 256, 2, 4>(g, p, st);
