@@ -25,7 +25,7 @@ namespace nimble {
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-enum { RING_DOUBLE = 0, RING_PINGPONG = 1, RING_SOLO = 2 };
+enum { RING_PINGPONG = 1, RING_SOLO = 2 };
 
 template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
@@ -225,42 +225,6 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     // the MFMAs above are opaque to the compiler's hazard handling: let the last results land
     // before anything reads the accumulators
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  } else {
-    bf16x8 xa[2][TM], wb[2][TN];
-#pragma unroll
-    for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(As[0][fr_a + j * 64]);
-#pragma unroll
-    for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(Bs[0][fr_b + i * 64]);
-
-    for (int base = 0; base < KS; base += S) {
-#pragma unroll
-      for (int u = 0; u < S; ++u) {  // unrolled: ring slot and register set are compile-time
-        const int ks = base + u;
-        if (ks < KS) {
-          const int cur = u & 1;
-          const int slot_next = (u + 1) % S, slot_free = (u + S - 1) % S;
-          if (ks + 1 < KS) {
-            // stage ks+1 may have min(S-3, KS-ks-2) younger stages still in flight behind it
-            if (KS - ks - 2 >= S - 3)
-              asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 3) * LD) : "memory");
-            else
-              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (ks + S - 1 < KS) dma(ks + S - 1, slot_free);
-#pragma unroll
-            for (int j = 0; j < TM; ++j) xa[cur ^ 1][j] = as_bf16x8(As[slot_next][fr_a + j * 64]);
-#pragma unroll
-            for (int i = 0; i < TN; ++i) wb[cur ^ 1][i] = as_bf16x8(Bs[slot_next][fr_b + i * 64]);
-          }
-#pragma unroll
-          for (int i = 0; i < TN; ++i)
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-              acc[i][j] =
-                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
-        }
-      }
-    }
   }
 
   // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
@@ -343,10 +307,10 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
 __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
-  // the 2 x 4 wave grid of the 256-wide tiles (wave tiles of 64..160 rows by 64 columns): the
-  // straight-line schedule with two fragment sets while accumulators and both sets fit in a
-  // wave's 256 registers (up to 128 rows per wave), the two-group ping-pong with one set above
-  constexpr int kPingPong = WGM == 2 && WGN == 4 ? (BM <= 256 ? RING_SOLO : RING_PINGPONG) : RING_DOUBLE;
+  // the straight-line schedule with two fragment sets wherever accumulators and both sets fit in
+  // a wave's 256 registers (wave tiles up to 128 rows by 64 columns); the two-group ping-pong
+  // with one set for the 288- and 320-row heights of the 256-wide tile
+  constexpr int kPingPong = WGM == 2 && WGN == 4 && BM > 256 ? RING_PINGPONG : RING_SOLO;
   constexpr int kPass = WGM * WGN * 16;  // rows per load pass: the ring holds whole passes of A
   constexpr int kBmp = (BM + kPass - 1) / kPass * kPass;
   __shared__ __attribute__((aligned(16))) uint4 smem[S * (kBmp + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles
