@@ -12,8 +12,10 @@ namespace nimble {
 // ---------------------------------------------------------------------------
 // Interior body of the large tiles.
 //   LDS: a ring of S = 4 stages, each BM + BN rows of 32 bf16 (4 chunks of 16
-//   bytes); chunk c of row r sits at slot c ^ ((r >> 2) & 3), so that the 16
-//   rows one quarter-wave reads at one logical chunk cover all 64 banks.
+//   bytes); chunk c of row r sits at slot c ^ ((r >> 1) & 3).  A fragment read
+//   (lane -> row lane & 15, chunk lane >> 4) then takes 4.3 clocks per wave
+//   instruction, the same as a linear read; without the swizzle, or with
+//   c ^ (r & 3) or c ^ ((r >> 2) & 3), it was measured at 6.3 (bank conflicts).
 //   Every wave issues its share of each stage as 16-byte-per-lane direct
 //   global->LDS loads (a wave instruction fills 16 rows x 64 bytes = 1 KiB of
 //   contiguous LDS); the swizzle is applied on the global side by choosing
@@ -67,7 +69,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // MEDGE (the last tile along M when r != 0): rows past M-1 are fetched from row M-1, so
   // every load stays in bounds; their products land in rows the epilogue never stores.
   const int ld_row = tid >> 2;
-  const int ld_c = (tid & 3) ^ ((ld_row >> 2) & 3);
+  const int ld_c = (tid & 3) ^ ((ld_row >> 1) & 3);
   uint32_t a_off[A_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
@@ -95,7 +97,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // fragment reads: lane -> row (lane & 15), logical chunk (lane >> 4)
   const int fr_row = lane & 15;
   const int fr_q = lane >> 4;
-  const int fr_phys = fr_q ^ ((fr_row >> 2) & 3);
+  const int fr_phys = fr_q ^ ((fr_row >> 1) & 3);
   const int fr_a = (wm * WM + fr_row) * 4 + fr_phys;
   const int fr_b = (wn * WN + fr_row) * 4 + fr_phys;
 
