@@ -8,7 +8,8 @@ from dataclasses import dataclass
 from typing import Optional, Sequence, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libnimble_hip.so")
+# NIMBLE_LIBRARY names another build of the same library (for A/B measurements)
+_LIB_PATH = os.environ.get("NIMBLE_LIBRARY") or os.path.join(_PKG, "libnimble_hip.so")
 _HEADERS = [os.path.join(os.path.dirname(_PKG), "include", h) for h in ("nimble.h", "nimble_vm.h")]
 
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU_ERF = 0, 1, 2

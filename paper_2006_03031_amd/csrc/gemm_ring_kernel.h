@@ -294,7 +294,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       const int c = lane & 7;
       const uint4 v = *(const uint4*)(region + h * (WM * 128) + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
       if (MEDGE && m0 + wm * WM + row >= g.M) continue;
-      *(uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + h * 64 + c * 8) = v;
+      uint4* dst = (uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + h * 64 + c * 8);
+      *dst = v;
     }
 }
 
