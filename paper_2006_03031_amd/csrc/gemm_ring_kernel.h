@@ -107,6 +107,20 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 #pragma unroll
     for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // The tile's BN bias values are fetched now, ahead of every other load, and parked in LDS behind
+  // the ring, so that the epilogue does not begin with a round trip to memory.  Issued as a
+  // volatile statement before the first ring load: the wait for stage 0 below then covers it
+  // (loads complete in order), and the compiler's own wait counting never sees it.  The 288- and
+  // 320-row tiles leave no LDS for it and load the bias in the epilogue.
+  constexpr bool BIAS_LDS = S * (BMP + BN) * 64 + BN * 2 <= 160 * 1024;
+  u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * 4);
+  const bool park_bias = BIAS_LDS && g.epilogue != NIMBLE_EPI_NONE && !g.out_f32;
+  uint2 bias_pre;
+  if (park_bias) {  // uniform branch; every lane loads (lanes past BN/4 repeat an earlier lane's 8 bytes)
+    const u16* src = (const u16*)g.bias + n0 + (tid & (BN / 4 - 1)) * 4;
+    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(bias_pre) : "v"(src) : "memory");
+  }
+
 #pragma unroll
   for (int s = 0; s < S - 1; ++s) {
     if constexpr (MODE == RING_SOLO)
@@ -120,6 +134,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   else
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  if (park_bias && tid < BN / 4) *(uint2*)(bias_lds + tid * 4) = bias_pre;  // read after the epilogue's barrier
 
   if constexpr (MODE == RING_PINGPONG) {
     // Waves w and w + NW/2 share a SIMD.  The workgroup runs in two groups half a step out of
@@ -238,7 +253,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 #pragma unroll
     for (int v = 0; v < 4; ++v) bias4[i][v] = 0.f;
     if (epi != NIMBLE_EPI_NONE) {
-      const uint2 bb = *(const uint2*)((const u16*)g.bias + n0 + wn * WN + i * 16 + fr_q * 4);
+      const uint2 bb = park_bias ? *(const uint2*)(bias_lds + wn * WN + i * 16 + fr_q * 4)
+                                 : *(const uint2*)((const u16*)g.bias + n0 + wn * WN + i * 16 + fr_q * 4);
       bias4[i][0] = bf2f((u16)(bb.x & 0xffff));
       bias4[i][1] = bf2f((u16)(bb.x >> 16));
       bias4[i][2] = bf2f((u16)(bb.y & 0xffff));
@@ -316,7 +332,10 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
   constexpr int kPingPong = WGM == 2 && WGN == 4 && BM > 256 ? RING_PINGPONG : RING_SOLO;
   constexpr int kPass = WGM * WGN * 16;  // rows per load pass: the ring holds whole passes of A
   constexpr int kBmp = (BM + kPass - 1) / kPass * kPass;
-  __shared__ __attribute__((aligned(16))) uint4 smem[S * (kBmp + BN) * 4];  // S >= 4: also holds the masked body's two 64-wide tiles
+  // the ring (which also holds the masked body's two 64-wide tiles), then BN bias values where they fit
+  constexpr int kRing = S * (kBmp + BN) * 4;
+  constexpr int kBias = kRing * 16 + BN * 2 <= 160 * 1024 ? BN / 8 : 0;
+  __shared__ __attribute__((aligned(16))) uint4 smem[kRing + kBias];
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
