@@ -139,8 +139,44 @@ def small_m_probe():
         torch.cuda.synchronize()
         us = s.elapsed_time(e) * 1e3 / reps
         nbytes = N * K * 2 + N * 2 + M * K * 2 + M * N * 2
+        # the same 64 launches (one per weight set, as 64 layers in a row would be) as one HIP graph:
+        # what the GPU needs once the host's per-call cost is out of the way
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(sets):
+                rt.dense(x, w[i], b, nb.EPI_BIAS, out=y)
+        graph.replay()
+        torch.cuda.synchronize()
+        s.record()
+        for _ in range(4):
+            graph.replay()
+        e.record()
+        torch.cuda.synchronize()
+        us_g = s.elapsed_time(e) * 1e3 / (4 * sets)
         out[f"dense_{K}x{N}_M{M}_rotating"] = {"us_per_call": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
-                                                 "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4)}
+                                                 "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4),
+                                                 "us_per_call_graph": round(us_g, 2),
+                                                 "hbm_frac_graph": round(nbytes / us_g / 1e3 / PEAK_HBM_GBPS, 4)}
+    del w
+    # the same at a size where HBM, not launch latency, is the bound: one 8192 x 8192 layer (134 MB)
+    N2 = K2 = 8192
+    w = torch.empty((4, N2, K2), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    b2 = torch.zeros((N2,), dtype=torch.bfloat16, device="cuda")
+    for M in (1, 16):
+        x = torch.empty((M, K2), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        y = torch.empty((M, N2), dtype=torch.bfloat16, device="cuda")
+        for i in range(4):
+            rt.dense(x, w[i], b2, nb.EPI_BIAS, out=y)
+        torch.cuda.synchronize()
+        s.record()
+        for i in range(16):
+            rt.dense(x, w[i % 4], b2, nb.EPI_BIAS, out=y)
+        e.record()
+        torch.cuda.synchronize()
+        us = s.elapsed_time(e) * 1e3 / 16
+        nbytes = N2 * K2 * 2 + N2 * 2 + M * K2 * 2 + M * N2 * 2
+        out[f"dense_{K2}x{N2}_M{M}_rotating"] = {"us_per_call": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                                                   "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4)}
     del w
     lw = wl.config2_weights()
     dw, db = _to_dev(lw.w), _to_dev(lw.b)
