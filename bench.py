@@ -294,6 +294,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--extra-only", action="store_true",
+                    help="run only the secondary probes (small-M dense, LSTM step, attention) and print them")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 512 MiB device copy (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -318,6 +320,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.extra_only:
+        print(json.dumps({"extra": small_m_probe()}))
+        return
     res = bench_config5(args.steps, args.warmup)
     line = {
         "metric": "dynamic-M dense TFLOP/s (bf16) over M sweep; % of MFMA/HBM roofline",
