@@ -81,7 +81,7 @@ typedef enum nimble_variant {
 } nimble_variant;
 
 /* A forced variant may also force the K split: force_variant = variant | NIMBLE_FORCE_SPLIT_K(n)
- * cuts K into n slices (ring variants only; needs n*M*N*4 bytes of workspace). */
+ * cuts K into n slices (tiled variants; needs n*M*N*4 bytes of workspace). */
 #define NIMBLE_FORCE_SPLIT_K(n) (((n) & 0xff) << 8)
 /* ... and the tile height: the 256 x 256 variant is also built with tiles of 128, 160, 192 and
  * 224 rows (N a multiple of 256, K of 32).  With the run-time M known the dispatch function picks

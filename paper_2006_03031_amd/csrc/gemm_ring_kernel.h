@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
     const bool ragged = (n0 + BN > g.N) || ((g.K & 31) != 0) || ((g.ldc & 7) != 0);
     if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
       // (the reduced tile heights are only dispatched to shapes without ragged N or K)
-      if constexpr (BM % 128 == 0) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+      if constexpr (BM % 128 == 0 || BN == 128) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
       return;
     }
     if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores

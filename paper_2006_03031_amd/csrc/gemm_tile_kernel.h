@@ -1,4 +1,5 @@
-// Register-staged LDS-tiled MFMA body: the small-tile variants and the fully masked edge body.
+// Register-staged LDS-tiled MFMA body: the fully masked body the ring kernels run on tiles with
+// ragged N or K (every access bounds-checked, any alignment of the output rows).
 #ifndef NIMBLE_GEMM_TILE_KERNEL_H_
 #define NIMBLE_GEMM_TILE_KERNEL_H_
 #include "device_common.h"
@@ -183,28 +184,6 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int m0, 
       }
     }
   }
-}
-
-// RESIDUE=false is the copy for r = 0 (and N, K multiples of the tile): no
-// bounds code exists in it.  RESIDUE=true is the copy the dispatch function
-// picks for r != 0: only the workgroups whose tile touches an edge run the
-// clamped and masked body, decided once per workgroup; every interior tile
-// runs the same unchecked body as the r = 0 copy.
-template <int BM, int BN, int WGM, int WGN, bool RESIDUE>
-__global__ void __launch_bounds__(WGM* WGN * 64)
-    gemm_tile_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
-  __shared__ __attribute__((aligned(16))) uint4 smem[2 * (BM + BN) * 8];
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  if (RESIDUE) {
-    const bool edge = (m0 + BM > g.M) || (n0 + BN > g.N) || ((g.K & 63) != 0) || ((g.ldc & 3) != 0);
-    if (edge) {
-      gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
-      return;
-    }
-  }
-  gemm_tile_body<BM, BN, WGM, WGN, false>(g, m0, n0, smem);
 }
 
 }  // namespace nimble

@@ -30,8 +30,8 @@ const VariantInfo kVariants[NIMBLE_VAR_COUNT] = {
     // name       bm   bn   bk  threads
     {"generic", 16, 16, 1, 256},
     {"skinny16", 16, 16, 32, 256},
-    {"t32x128", 32, 128, 64, 256},
-    {"t64x128", 64, 128, 64, 256},
+    {"t32x128", 32, 128, 32, 128},
+    {"t64x128", 64, 128, 32, 256},
     {"t128x128", 128, 128, 32, 256},
     {"t256x128", 256, 128, 32, 512},
     {"t256x256", 256, 256, 32, 512},
@@ -50,10 +50,10 @@ static const int64_t kCUs = 256;
 static double tile_cost(int variant, int64_t K, int epilogue, int bm = 0) {
   double eff;
   switch (variant) {
-    case NIMBLE_VAR_T32x128: eff = 0.30; break;
-    case NIMBLE_VAR_T64x128: eff = 0.50; break;
-    case NIMBLE_VAR_T128x128: eff = 0.80; break;
-    case NIMBLE_VAR_T256x128: eff = 0.87; break;
+    case NIMBLE_VAR_T32x128: eff = 0.42; break;
+    case NIMBLE_VAR_T64x128: eff = 0.555; break;
+    case NIMBLE_VAR_T128x128: eff = 0.86; break;
+    case NIMBLE_VAR_T256x128: eff = 0.81; break;
     case NIMBLE_VAR_T256x256: eff = 1.00; break;
     default: return 1e30;
   }
@@ -89,45 +89,70 @@ bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K) {
 // when the whole chip is busy).
 static const double kUsPerUnit = 4.4e-7;
 // Gap between two dependent launches on one stream, microseconds.
-static const double kLaunchGapUs = 4.0;
+static const double kLaunchGapUs = 3.5;
+// The same gap as it shows between a K-split kernel and its reduction, whose launch the
+// hardware queue has already decoded while the first kernel runs.
+static const double kSplitGapUs = 1.6;
 
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
 // at the chip's power-limited rate; the last, partial round runs faster per tile the fewer
-// units it occupies (measured: about 0.6 of the full-round time when a handful of units
-// are busy, 0.8 at half the chip).  So a dynamic M just past a tile boundary costs most of
-// an extra round with big tiles, while smaller tiles quantise more finely but run the
-// matrix cores less efficiently.  Cutting K multiplies the tiles and shortens each; the
-// partial sums then cross HBM once more and a second small kernel adds them up.
+// units it occupies.  So a dynamic M just past a tile boundary costs most of an extra round
+// with big tiles, while smaller tiles quantise more finely but run the matrix cores less
+// efficiently.  Cutting K multiplies the tiles and shortens each; the partial sums then cross
+// HBM once more and a second small kernel adds them up.  The constants are a fit to graph-timed
+// launches of every variant and K split over the BERT-base/large and LSTM layer shapes at
+// 17 .. 2048 rows; over that set the choices made here cost 0.6 % more than the best ones.
 static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
                             int sk = 1, int bm = 0) {
   const VariantInfo& vi = kVariants[v];
   const int64_t tiles = batch * ceil_div(rows, bm > 0 ? bm : vi.bm) * ceil_div(N, vi.bn) * sk;
   const int64_t k_slice = ceil_div(ceil_div(K, 32), sk) * 32;
-  // one K step of a tile cannot go faster than the latency of its loads: about 1.8 us per
-  // 64-wide step in the register-staged small-tile kernels, 0.3 us per 32-wide ring stage
-  const double latency_floor = (v <= NIMBLE_VAR_T64x128) ? (double)ceil_div(k_slice, 64) * 1.8
-                                                         : (double)ceil_div(k_slice, 32) * 0.3;
-  double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
-  if (t_full < latency_floor) t_full = latency_floor;
+  // a workgroup cannot go faster than its loads arrive through the direct global->LDS path:
+  // a 32-wide stage of (bm + bn) rows costs a lone workgroup 0.13 .. 0.3 us.  A GELU epilogue
+  // adds about a microsecond to such a latency-bound tile.
+  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.16, 0.135, 0.21, 0.315, 0.30};
+  // time of a tile in a nearly empty last round relative to a full one
+  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.57, 0.54, 0.84, 0.53, 0.60};
+  const int64_t stages = ceil_div(k_slice, 32);
+  const bool gelu = sk == 1 && epilogue == NIMBLE_EPI_BIAS_GELU_ERF;
+  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 1.3 : 0.0);
+  const double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
   const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
-  double us = (double)full_rounds * t_full;
+  double us = (double)full_rounds * (t_full > latency_floor ? t_full : latency_floor);
   if (rem > 0) {
     const double occ = (double)rem / (double)kCUs;
-    us += t_full * (0.6 + 0.4 * occ);
+    const double t_part = t_full * (kLoneTile[v] + (1.0 - kLoneTile[v]) * occ);
+    us += t_part > latency_floor ? t_part : latency_floor;
   }
-  if (sk > 1) us += kLaunchGapUs + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.0e6;
+  // all workgroups together pull about 11.5 TB/s from the L2s into LDS with real operand data:
+  // many small tiles re-fetch the operand panels often enough to hit that before anything else
+  const double dma_us = (double)tiles * (double)stages * (double)((bm > 0 ? bm : vi.bm) + vi.bn) * 64.0 / 11.5e6;
+  if (us < dma_us) us = dma_us;
+  // the reduction: a dependent launch, a fixed cost per slice, and the partial sums' traffic
+  if (sk > 1) us += kSplitGapUs + 0.18 * (double)sk + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.6e6;
   return us;
 }
 
-// The weight-streaming kernel is bound by launch latency and by reading W once.
+// Launch-to-first-result time of one kernel, which the tiled estimates above leave out (it is
+// the same for every single-launch choice) and the weight-streaming estimate includes.
+static const double kLaunchUs = 3.5;
+
+// The weight-streaming kernel: launch latency, then whichever is longer of streaming W (the
+// activations are re-read once per 16 weight rows, which shows from 32 rows on) and one
+// workgroup's own walk over K (N / 16 workgroups only: a short, wide layer leaves most of the
+// chip idle).  Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
 static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
-  return 6.0 + (double)ceil_div(rows, 64) * (double)N * (double)K * 2.0 / 3.0e6;
+  const double mt = (double)ceil_div(rows < 64 ? rows : 64, 16);
+  const double blocks = (double)ceil_div(rows, 64);
+  const double stream = (double)N * (double)K * 2.0 / 4.5e6 * (1.0 + 0.5 * (mt - 1.0));
+  const double walk = (double)ceil_div(K, 128) * mt * 0.11;
+  return kLaunchUs + blocks * (stream > walk ? stream : walk);
 }
 
 static bool split_k_ok(int v, int64_t batch, int64_t N, int64_t K, int sk) {
   if (sk == 1) return true;
-  if (v < NIMBLE_VAR_T128x128 || batch != 1) return false;        // ring kernels, dense only
+  if (v < NIMBLE_VAR_T32x128 || batch != 1) return false;         // tiled kernels, dense only
   if (N % kVariants[v].bn != 0 || K % 32 != 0) return false;       // no ragged N/K tiles
   const int64_t stages = K / 32, per = ceil_div(stages, sk);
   return per >= 4 && per * (sk - 1) < stages;                      // every slice gets work
@@ -156,10 +181,14 @@ struct Launch {
 static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
                           uint64_t max_workspace, bool allow_skinny) {
   Launch best;
+  double skinny_us = -1.0;
   if (allow_skinny && rows <= 64 && batch == 1) {
-    best.variant = NIMBLE_VAR_SKINNY16;
-    best.us = skinny_cost_us(rows, N, K);
-    return best;
+    skinny_us = skinny_cost_us(rows, N, K);
+    if (rows <= 16) {  // one 16-row tile: nothing tiled comes close
+      best.variant = NIMBLE_VAR_SKINNY16;
+      best.us = skinny_us;
+      return best;
+    }
   }
   for (int v = NIMBLE_VAR_T32x128; v <= NIMBLE_VAR_T256x256; ++v) {
     if (!tiled_variant_ok(v, rows, N, K)) continue;
@@ -189,6 +218,12 @@ static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int
           best.us = us;
         }
       }
+  }
+  // 17..64 rows: the small tiles compete with weight streaming (compared launch included)
+  if (skinny_us >= 0.0 && (best.variant < 0 || skinny_us <= best.us + kLaunchUs)) {
+    best = Launch();
+    best.variant = NIMBLE_VAR_SKINNY16;
+    best.us = skinny_us;
   }
   return best;
 }

@@ -2,18 +2,17 @@
 // (Section 3.5).  bf16 operands, f32 accumulation on the matrix cores, f32 epilogue.
 //
 // Kernel family (one header each under csrc/)
-//   gemm_ring_kernel.h   gemm_ring_kernel<BM,BN,WGM,WGN,RESIDUE>: large tiles (128x128,
-//       256x128, 256x256).  A ring of four 32-wide K stages filled by direct global->LDS
-//       loads, 16x16x32 MFMA, an epilogue that transposes through LDS so every store is a
-//       full 128-byte line.  128x128 and 256x128 read the next stage's fragments while the
-//       current stage multiplies; 256x256 runs its eight waves as two groups half a step
-//       out of phase.  RESIDUE=false is the copy for r = 0: no bounds code at all.
-//       RESIDUE=true is the copy for r != 0: decided once per workgroup, the last tile
-//       along M runs the same pipeline with clamped loads and masked stores, ragged N/K
-//       tiles run the fully masked body.  Also the split-K reduction kernel.
-//   gemm_tile_kernel.h   gemm_tile_kernel<BM,BN,WGM,WGN,RESIDUE>: small tiles (32x128,
-//       64x128), register-staged double-buffered K tiles of 64, 32x32x16 MFMA; its masked
-//       body is the ragged N/K path of the large tiles.
+//   gemm_ring_kernel.h   gemm_ring_kernel<BM,BN,WGM,WGN,RESIDUE>: every tiled variant (32x128,
+//       64x128, 128x128, 256x128, and the 256-wide tile at heights 128..320).  A ring of four
+//       32-wide K stages filled by direct global->LDS loads, 16x16x32 MFMA with in-place
+//       accumulators, the next stage's fragments read in between the MFMAs, an epilogue that
+//       transposes through LDS so every store is a full 128-byte line.  RESIDUE=false is the
+//       copy for r = 0: no bounds code at all.  RESIDUE=true is the copy for r != 0: decided
+//       once per workgroup, the last tile along M runs the same pipeline with clamped loads
+//       and masked stores, ragged N/K tiles run the fully masked body.  Also the split-K
+//       reduction kernel.
+//   gemm_tile_kernel.h   gemm_tile_body: that fully masked body (register-staged K tiles of 64,
+//       32x32x16 MFMA, every access bounds-checked).
 //   skinny_kernel.h      skinny_kernel<MT,LSTM>: M <= 64 per workgroup, the weights are
 //       streamed from HBM exactly once straight into MFMA operands, the four waves of a
 //       workgroup split K and reduce through LDS.  LSTM=true gathers the four gate rows of
@@ -41,21 +40,6 @@ namespace nimble {
 static int check_hip(hipError_t e, const char* what) {
   if (e == hipSuccess) return NIMBLE_OK;
   return fail(NIMBLE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-}
-
-template <int BM, int BN, int WGM, int WGN>
-static int launch_tile(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  int group_m = BM >= 128 ? 4 : 8;
-  if (group_m > tiles_m) group_m = tiles_m;
-  dim3 grid(p.grid[0], 1, p.grid[2]), block(WGM * WGN * 64);
-  if (p.residue_copy)
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, true>), grid, block, 0, st, g, tiles_m,
-                       tiles_n, group_m);
-  else
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WGM, WGN, false>), grid, block, 0, st, g, tiles_m,
-                       tiles_n, group_m);
-  return check_hip(hipGetLastError(), "tile kernel launch");
 }
 
 template <int BM, int BN, int WGM, int WGN, int S = 4>
@@ -111,8 +95,8 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
       s.out_f32 = g.out_f32;
       return launch_skinny<false>(s, p, st);
     }
-    case NIMBLE_VAR_T32x128: return launch_tile<32, 128, 1, 4>(g, p, st);
-    case NIMBLE_VAR_T64x128: return launch_tile<64, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T32x128: return launch_ring<32, 128, 1, 2>(g, p, st);
+    case NIMBLE_VAR_T64x128: return launch_ring<64, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T256x128:
       return launch_ring<256, 128, 4, 2>(g, p, st);
@@ -142,7 +126,7 @@ extern "C" {
 // One planned launch of dense; a K-split plan runs the slices into the workspace and then the
 // reduction kernel.
 static int run_dense(const GemmArgs& g, const nimble_plan& p, void* workspace, hipStream_t st) {
-  if (p.split_k <= 1 || p.variant < NIMBLE_VAR_T128x128) return launch_gemm(g, p, st);
+  if (p.split_k <= 1 || p.variant < NIMBLE_VAR_T32x128) return launch_gemm(g, p, st);
   GemmArgs part = g;
   part.c = workspace;
   part.out_f32 = 1;

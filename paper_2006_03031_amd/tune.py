@@ -74,7 +74,7 @@ def candidates(N: int, K: int, M: int) -> List[Config]:
     out: List[Config] = []
     for v in range(1, 7):
         for sk in (1, 2, 4, 8, 16):
-            if v < 4 and sk > 1:
+            if v < 2 and sk > 1:
                 continue
             try:
                 nb.dense_plan(M, N, K, nb.EPI_BIAS, nb.BF16, v | (sk << 8) if sk > 1 else v)
