@@ -255,6 +255,93 @@ def small_m_probe():
     return out
 
 
+def achievable_peaks():
+    """What this GPU sustains on a register-only bf16 MFMA loop (one and two waves per SIMD, real
+    operand data) and on a plain streaming read of 2 GiB: the ceilings any kernel here works
+    under, printed next to the nominal peaks the roofline fractions are taken against."""
+    import torch
+
+    import paper_2006_03031_amd as nb
+
+    out = {}
+    seed = torch.empty(32768, dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+    sink = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    for waves in (1, 2):
+        nb.nimble_probe_mfma_bf16(seed.data_ptr(), sink.data_ptr(), waves, 4000, stream)
+        torch.cuda.synchronize()
+        s.record()
+        flops = nb.nimble_probe_mfma_bf16(seed.data_ptr(), sink.data_ptr(), waves, 20000, stream)
+        e.record()
+        torch.cuda.synchronize()
+        out[f"mfma_bf16_TFLOPs_{waves}_wave_per_simd"] = round(flops / (s.elapsed_time(e) * 1e-3) / 1e12, 1)
+    buf = torch.ones(2 << 30, dtype=torch.uint8, device="cuda")
+    nb.nimble_probe_hbm_read(buf.data_ptr(), buf.numel(), sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    s.record()
+    for _ in range(8):
+        nb.nimble_probe_hbm_read(buf.data_ptr(), buf.numel(), sink.data_ptr(), stream)
+    e.record()
+    torch.cuda.synchronize()
+    out["hbm_read_GBps"] = round(8 * buf.numel() / (s.elapsed_time(e) * 1e-3) / 1e9, 1)
+    return out
+
+
+def config_1_and_3_probe():
+    """Configs 1 and 3 at their own sizes: microseconds per call with the launches of one pass
+    replayed as a HIP graph (what the GPU needs) and launched one by one (what a Python caller
+    sees).  Config 1 (128 -> 128, M <= 64) is launch-bound: 33 KB of weights are 4 ns of HBM time."""
+    import numpy as np
+    import torch
+
+    import paper_2006_03031_amd as nb
+    import workloads as wl
+    from paper_2006_03031_amd import runtime as rt
+    from paper_2006_03031_amd.tune import _time_us
+
+    out = {}
+    calls = wl.config1_calls()
+    w, b = _to_dev(calls[0].w), _to_dev(calls[0].b)
+    xs = [_to_dev(c.x) for c in calls]
+    ys = [torch.empty((x.shape[0], 128), dtype=torch.bfloat16, device="cuda") for x in xs]
+
+    def pass1():
+        for x, y in zip(xs, ys):
+            rt.dense(x, w, b, nb.EPI_BIAS, out=y)
+    pass1()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        pass1()
+    torch.cuda.synchronize()
+    out["config1_dense_128x128"] = {"us_per_call_eager": round((time.perf_counter() - t0) * 1e6 / (8 * len(xs)), 2),
+                                    "us_per_call_graph": round(_time_us(pass1, reps=1) / len(xs), 2)}
+    epi = {"bias": nb.EPI_BIAS, "bias_gelu": nb.EPI_BIAS_GELU_ERF}
+    weights = [(_to_dev(wb[0]), _to_dev(wb[1]), K, N, epi[e]) for i, (n, K, N, e) in enumerate(wl.BERT_BASE_GEMMS)
+               for wb in (wl.dense_weights(3, i, N, K),)]
+    for L in (1, 16, 128, 384, 512):
+        bufs = [(torch.empty((L, K), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1),
+                 torch.empty((L, N), dtype=torch.bfloat16, device="cuda")) for _, _, K, N, _ in weights]
+
+        def layer():
+            for (wt, bt, K, N, e), (x, y) in zip(weights, bufs):
+                rt.dense(x, wt, bt, e, out=y)
+        us = _time_us(layer, reps=8)
+        flops = 2.0 * L * sum(K * N for _, _, K, N, _ in weights)
+        plans = [nb.dense_plan(L, N, K, e) for _, _, K, N, e in weights]
+        out[f"config3_bert_base_L{L}"] = {"us_4_gemms_graph": round(us, 2), "TFLOPs": round(flops / us / 1e6, 1),
+                                          "plans": [pl.name + (f"/sk{pl.split_k}" if pl.split_k > 1 and pl.variant > 1 else "") for pl in plans]}
+    return out
+
+
+def _extras():
+    out = small_m_probe()
+    out.update(config_1_and_3_probe())
+    out["achievable"] = achievable_peaks()
+    return out
+
+
 def cpu_baseline():
     """The oracle as it stands, timed on the host cores on a bounded sample of the
     same workload: the median-M and the largest-M draw, both FFN GEMMs."""
@@ -321,7 +408,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.extra_only:
-        print(json.dumps({"extra": small_m_probe()}))
+        print(json.dumps({"extra": _extras()}))
         return
     res = bench_config5(args.steps, args.warmup)
     line = {
@@ -336,7 +423,7 @@ def main():
         "roofline": res["roofline"],
     }
     if not args.no_extra:
-        line["extra"] = small_m_probe()
+        line["extra"] = _extras()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline()
     print(json.dumps(line))

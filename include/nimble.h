@@ -224,6 +224,22 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
                           const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t Ix,
                           int64_t H, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ----------------------------------------------------------------------------
+ * Calibration probes: not part of the method.  The benchmark times them to print
+ * what this GPU sustains next to the nominal peaks its roofline fractions use.
+ * -------------------------------------------------------------------------- */
+
+/* Register-only bf16 MFMA loop: 256 workgroups of 4 * waves_per_simd waves (1, 2 or 4), each
+ * wave issuing iters * 32 MFMAs of 16x16x32.  seed: device, 64 KiB of bf16 operand data (any
+ * finite values); sink: device, 1 MiB, overwritten.  *flops receives the flop count of the
+ * launch.  Asynchronous on `stream`; the caller times it. */
+int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int iters,
+                           double* flops, void* stream);
+
+/* Plain streaming read of `bytes` (a multiple of 16) from buf (device, 16-byte aligned).
+ * sink: device, 16 bytes.  Asynchronous on `stream`; the caller times it. */
+int nimble_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,6 +20,7 @@
 //   misc_kernels.h       generic_kernel (any shape and stride, one thread per output),
 //       softmax_rows_kernel (f32 scores -> bf16 probabilities), attention64_kernel (fused
 //       softmax(alpha Q.K^T).V for head dimension 64).
+//   probe_kernels.h      calibration probes: a register-only MFMA loop and a streaming read.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -30,6 +31,7 @@
 #include "gemm_tile_kernel.h"
 #include "misc_kernels.h"
 #include "nimble_internal.h"
+#include "probe_kernels.h"
 #include "skinny_kernel.h"
 
 namespace nimble {
@@ -305,6 +307,40 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
   s.H = (int)H;
   s.epilogue = NIMBLE_EPI_BIAS;
   return launch_skinny<true>(s, p, (hipStream_t)stream);
+}
+
+int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int iters, double* flops,
+                           void* stream) {
+  clear_error();
+  if (!seed || !sink || !flops) return fail(NIMBLE_ERR_NULL, "null pointer");
+  if (misaligned(seed) || misaligned(sink)) return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (iters < 1 || iters > (1 << 24)) return fail(NIMBLE_ERR_ARG, "iters out of range");
+  const dim3 grid(256);
+  const uint4* sd = (const uint4*)seed;
+  float* sk = (float*)sink;
+  switch (waves_per_simd) {
+    case 1: hipLaunchKernelGGL(probe_mfma_kernel<256>, grid, dim3(256), 0, (hipStream_t)stream, sd, sk, iters); break;
+    case 2: hipLaunchKernelGGL(probe_mfma_kernel<512>, grid, dim3(512), 0, (hipStream_t)stream, sd, sk, iters); break;
+    case 4: hipLaunchKernelGGL(probe_mfma_kernel<1024>, grid, dim3(1024), 0, (hipStream_t)stream, sd, sk, iters); break;
+    default: return fail(NIMBLE_ERR_ARG, "waves_per_simd must be 1, 2 or 4");
+  }
+  // per wave and pass: 32 MFMAs of 16 x 16 x 32 multiply-adds
+  *flops = 256.0 * 4.0 * waves_per_simd * (double)iters * 32.0 * (2.0 * 16 * 16 * 32);
+  return check_hip(hipGetLastError(), "probe launch");
+}
+
+int nimble_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  clear_error();
+  if (!buf || !sink) return fail(NIMBLE_ERR_NULL, "null pointer");
+  if (misaligned(buf) || misaligned(sink)) return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (bytes % 16 != 0) return fail(NIMBLE_ERR_ARG, "bytes must be a multiple of 16");
+  const long long n16 = (long long)(bytes / 16);
+  if (n16 == 0) return NIMBLE_OK;
+  const long long blocks = (n16 + 1023) / 1024;
+  if (blocks > 0x7fffffffll) return fail(NIMBLE_ERR_ARG, "buffer too large");
+  hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)buf, n16, (uint4*)sink);
+  return check_hip(hipGetLastError(), "probe launch");
 }
 
 }  // extern "C"
