@@ -53,6 +53,7 @@ def _load():
         lib.oracle_batch_matmul.argtypes = [fp, fp, fp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_float]
         lib.oracle_softmax_rows.argtypes = [fp, fp, i64, i64]
         lib.oracle_lstm_step.argtypes = [fp, fp, fp, fp, fp, fp, fp, fp, i64, i64, i64]
+        lib.oracle_lstm_step_pre.argtypes = [fp, fp, fp, fp, fp, fp, fp, i64, i64]
         lib.oracle_dense_shape.argtypes = [ip, ctypes.c_int, ip, ctypes.c_int, ip]
         lib.oracle_batch_matmul_shape.argtypes = [ip, ctypes.c_int, ip, ctypes.c_int, ctypes.c_int, ip]
         lib.oracle_lstm_shape.argtypes = [ip, ip, ip, ip, ip, ip]
@@ -171,6 +172,24 @@ def lstm_step(x, h, w, b, c) -> Tuple[np.ndarray, np.ndarray]:
     g = np.empty((B, 4 * H), dtype=np.float32)
     _check(_load().oracle_lstm_step(_p(x), _p(h), _p(w), _p(b), _p(c), _p(h_out), _p(c_out),
                                     _p(g), B, Ix, H), "lstm_step")
+    return h_out, c_out
+
+
+def lstm_step_pre(pre, h, wh, c) -> Tuple[np.ndarray, np.ndarray]:
+    """One LSTM cell step from gates whose input share pre = x.Wx^T + b [B, 4H] was computed
+    beforehand (for all tokens in one product); wh [4H, H] are the recurrent columns of the
+    fused weight.  Returns (h', c')."""
+    pre, h, wh, c = _f(pre), _f(h), _f(wh), _f(c)
+    if h.ndim != 2 or pre.ndim != 2 or wh.ndim != 2 or c.ndim != 2:
+        raise OracleShapeError("rank-2 operands expected")
+    B, H = h.shape
+    if pre.shape != (B, 4 * H) or wh.shape != (4 * H, H) or c.shape != (B, H):
+        raise OracleShapeError("pre must be (B,4H), wh (4H,H), c (B,H)")
+    h_out = np.empty((B, H), dtype=np.float32)
+    c_out = np.empty((B, H), dtype=np.float32)
+    g = np.empty((B, 4 * H), dtype=np.float32)
+    _check(_load().oracle_lstm_step_pre(_p(pre), _p(h), _p(wh), _p(c), _p(h_out), _p(c_out), _p(g), B, H),
+           "lstm_step_pre")
     return h_out, c_out
 
 

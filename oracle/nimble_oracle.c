@@ -143,6 +143,36 @@ int oracle_lstm_step(const float *x, const float *h, const float *w, const float
   return ORACLE_OK;
 }
 
+/*
+ * The same cell with the input's share of the gates computed beforehand for every token of the
+ * sequence in one product (the evaluation section's remark on batching the inputs' matrix
+ * multiplication along the sequence):  pre = x . Wx^T + b  is given,  G = pre + h . Wh^T  with
+ * Wh [4H, H] the recurrent columns of the fused weight; gate order and update as above.
+ */
+int oracle_lstm_step_pre(const float *pre, const float *h, const float *wh, const float *c,
+                         float *h_out, float *c_out, float *g_scratch, int64_t B, int64_t H) {
+  if (B < 0 || H < 0) return ORACLE_ERR_ARG;
+  const int64_t N = 4 * H;
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < B; ++m) {
+    for (int64_t n = 0; n < N; ++n) {
+      float acc = 0.0f;
+      for (int64_t k = 0; k < H; ++k) acc += h[m * H + k] * wh[n * H + k];
+      g_scratch[m * N + n] = pre[m * N + n] + acc;
+    }
+    for (int64_t j = 0; j < H; ++j) {
+      const float gi = g_scratch[m * N + j];
+      const float gf = g_scratch[m * N + H + j];
+      const float gg = g_scratch[m * N + 2 * H + j];
+      const float go = g_scratch[m * N + 3 * H + j];
+      const float cn = sigmoid1(gf) * c[m * H + j] + sigmoid1(gi) * tanhf(gg);
+      c_out[m * H + j] = cn;
+      h_out[m * H + j] = sigmoid1(go) * tanhf(cn);
+    }
+  }
+  return ORACLE_OK;
+}
+
 /* ------------------------------------------------------------------------
  * Integer side.
  * ---------------------------------------------------------------------- */

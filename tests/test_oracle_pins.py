@@ -348,6 +348,73 @@ def test_lstm_gates_are_the_dense_of_the_concatenation():
     assert np.max(np.abs(hn - sg(o) * np.tanh(c_ref))) < 1e-6
 
 
+# ------------------------------------------------------------------ LSTM cell, input share of the gates given
+def test_lstm_pre_closed_forms_and_gate_blocks():
+    rng = np.random.default_rng(22)
+    B = 3
+    h0, c0 = _rand(rng, (B, H)), _rand(rng, (B, H))
+    wh = np.zeros((4 * H, H), np.float32)
+    big = 30.0
+    c64 = c0.astype(np.float64)
+
+    def run(**blocks):
+        pre = np.zeros((B, 4 * H), np.float32)
+        for name, val in blocks.items():
+            j = "ifgo".index(name)
+            pre[:, j * H:(j + 1) * H] = val
+        return oracle.lstm_step_pre(pre, h0, wh, c0)
+
+    h, c = run()  # all gates 0: i = f = o = 1/2, g = 0
+    assert np.array_equal(c, c0 / 2)
+    assert np.max(np.abs(h - 0.5 * np.tanh(c64 / 2))) < 1e-7
+    h, c = run(f=big, i=-big)  # carried over
+    assert np.max(np.abs(c - c0)) < 1e-7
+    h, c = run(o=big)
+    assert np.max(np.abs(h - np.tanh(c64 / 2))) < 1e-7
+    h, c = run(i=big, g=-big, f=-big)
+    assert np.max(np.abs(c + 1.0)) < 1e-6
+
+
+def test_lstm_pre_recurrent_weight_indexing():
+    # a single one at row (g block, unit 3), column a of wh picks h[:, a]; pre is per row AND per gate column
+    rng = np.random.default_rng(23)
+    B = 4
+    h0 = _rand(rng, (B, H))
+    c0 = np.zeros((B, H), np.float32)
+    wh = np.zeros((4 * H, H), np.float32)
+    wh[2 * H + 3, 5] = 1.0
+    pre = np.zeros((B, 4 * H), np.float32)
+    hn, cn = oracle.lstm_step_pre(pre, h0, wh, c0)
+    assert np.max(np.abs(cn[:, 3] - 0.5 * np.tanh(h0[:, 5].astype(np.float64)))) < 1e-7
+    assert np.array_equal(np.delete(cn, 3, axis=1), np.zeros((B, H - 1), np.float32))
+    # pre is added, not overwritten: the same unit with pre = -h[:,5] gives g = 0
+    pre[:, 2 * H + 3] = -h0[:, 5]
+    hn, cn = oracle.lstm_step_pre(pre, h0, wh, c0)
+    assert np.array_equal(cn, np.zeros_like(cn))
+    # pre of one row only moves that row
+    pre = np.zeros((B, 4 * H), np.float32)
+    pre[1, 2 * H + 6] = 30.0
+    wh[:] = 0
+    hn, cn = oracle.lstm_step_pre(pre, h0, wh, c0)
+    assert abs(cn[1, 6] - 0.5) < 1e-7 and np.count_nonzero(cn) == 1
+
+
+def test_lstm_pre_equals_the_fused_cell_when_pre_is_the_input_product():
+    # [x | h] . W^T + b = (x . Wx^T + b) + h . Wh^T: the step from precomputed input gates must
+    # agree with the fused step (pinned above) up to the order of the float32 additions.
+    rng = np.random.default_rng(24)
+    B = 5
+    x, h0, c0 = _rand(rng, (B, IX)), _rand(rng, (B, H)), _rand(rng, (B, H))
+    w, b = _rand(rng, (4 * H, IX + H)), _rand(rng, (4 * H,))
+    h_ref, c_ref = oracle.lstm_step(x, h0, w, b, c0)
+    pre = oracle.dense(x, np.ascontiguousarray(w[:, :IX]), b, "bias")
+    hn, cn = oracle.lstm_step_pre(pre, h0, np.ascontiguousarray(w[:, IX:]), c0)
+    assert np.max(np.abs(cn - c_ref)) < 2e-6
+    assert np.max(np.abs(hn - h_ref)) < 2e-6
+    with pytest.raises(oracle.OracleShapeError):
+        oracle.lstm_step_pre(pre[:, :-1], h0, w[:, IX:], c0)
+
+
 # ------------------------------------------------------------------ integer side
 def test_dense_shape_function_every_M_up_to_513():
     for M in range(0, 514):
