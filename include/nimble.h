@@ -224,6 +224,18 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
                           const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t Ix,
                           int64_t H, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same cell when the inputs' share of the gates has been computed for every token of the
+ * sequence in one dense call (the evaluation section's remark that the inputs' matrix
+ * multiplication can be batched along the sequence: x_all [T*B, Ix] . w_x^T + bias with f32
+ * output, M = T*B dynamic): per token only the recurrent half of the weight is streamed.
+ *   G = pre + h_prev . w_h^T;  cell update as above.
+ * pre [B,4H] f32 (bias already added; gate blocks i, f, g, o), h_prev [B,H] bf16,
+ * w_h [4H,H] bf16 (the recurrent columns of the fused weight, contiguous), c_prev / c_out
+ * [B,H] f32 (may alias), h_out [B,H] bf16 (must not alias h_prev).  H a multiple of 8. */
+int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w_h,
+                              const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t H,
+                              void* stream);
+
 /* ----------------------------------------------------------------------------
  * Calibration probes: not part of the method.  The benchmark times them to print
  * what this GPU sustains next to the nominal peaks its roofline fractions use.

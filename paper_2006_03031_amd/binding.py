@@ -104,6 +104,7 @@ def load():
     lib.nimble_softmax_rows_dyn.argtypes = [vp, vp, i64, i64, vp]
     lib.nimble_attention_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.c_float, vp]
     lib.nimble_lstm_gates_dyn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
+    lib.nimble_lstm_gates_pre_dyn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp]
     lib.nimble_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.nimble_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     _lib = lib
@@ -276,6 +277,11 @@ def nimble_lstm_gates_dyn(x: int, h_prev: int, w: int, bias: int, c_prev: int, c
                           stream: int = 0) -> None:
     _check(load().nimble_lstm_gates_dyn(x, h_prev, w, bias, c_prev, c_out, h_out, B, Ix, H, workspace,
                                         workspace_bytes, stream))
+
+
+def nimble_lstm_gates_pre_dyn(pre: int, h_prev: int, w_h: int, c_prev: int, c_out: int, h_out: int, B: int, H: int,
+                              stream: int = 0) -> None:
+    _check(load().nimble_lstm_gates_pre_dyn(pre, h_prev, w_h, c_prev, c_out, h_out, B, H, stream))
 
 
 def nimble_probe_mfma_bf16(seed: int, sink: int, waves_per_simd: int, iters: int, stream: int = 0) -> float:

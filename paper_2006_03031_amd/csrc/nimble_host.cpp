@@ -50,18 +50,18 @@ static const int64_t kCUs = 256;
 static double tile_cost(int variant, int64_t K, int epilogue, int bm = 0) {
   double eff;
   switch (variant) {
-    case NIMBLE_VAR_T32x128: eff = 0.42; break;
-    case NIMBLE_VAR_T64x128: eff = 0.555; break;
-    case NIMBLE_VAR_T128x128: eff = 0.86; break;
-    case NIMBLE_VAR_T256x128: eff = 0.81; break;
-    case NIMBLE_VAR_T256x256: eff = 1.00; break;
+    case NIMBLE_VAR_T32x128: eff = 0.394; break;
+    case NIMBLE_VAR_T64x128: eff = 0.527; break;
+    case NIMBLE_VAR_T128x128: eff = 0.817; break;
+    case NIMBLE_VAR_T256x128: eff = 0.848; break;
+    case NIMBLE_VAR_T256x256: eff = 1.05; break;
     default: return 1e30;
   }
   const double k0 = (epilogue == NIMBLE_EPI_BIAS_GELU_ERF) ? 256.0 : 128.0;
   // a tile of another height loads the same weight panel for fewer or more rows: measured
-  // time(bm) / time(256) = 0.28 + 0.72 bm/256 for the 256-wide tile (bm = 128..320)
+  // time(bm) / time(256) = 0.16 + 0.84 bm/256 for the 256-wide tile (bm = 128..320)
   const double height = (bm > 0 && bm != kVariants[variant].bm)
-                            ? 0.28 + 0.72 * (double)bm / (double)kVariants[variant].bm : 1.0;
+                            ? 0.158 + 0.842 * (double)bm / (double)kVariants[variant].bm : 1.0;
   return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) * height / eff;
 }
 
@@ -92,7 +92,12 @@ static const double kUsPerUnit = 4.4e-7;
 static const double kLaunchGapUs = 3.5;
 // The same gap as it shows between a K-split kernel and its reduction, whose launch the
 // hardware queue has already decoded while the first kernel runs.
-static const double kSplitGapUs = 1.6;
+static const double kSplitGapUs = 1.44;
+
+// Weights above this size are taken to come from HBM on every call (the L2s hold 32 MB, the
+// memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
+// as cache-resident, which is what a layer loop or a token loop sees.
+static const double kCachedWeightBytes = 64e6;
 
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
@@ -111,12 +116,12 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
   // a workgroup cannot go faster than its loads arrive through the direct global->LDS path:
   // a 32-wide stage of (bm + bn) rows costs a lone workgroup 0.13 .. 0.3 us.  A GELU epilogue
   // adds about a microsecond to such a latency-bound tile.
-  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.16, 0.135, 0.21, 0.315, 0.30};
+  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.181, 0.104, 0.21, 0.315, 0.30};
   // time of a tile in a nearly empty last round relative to a full one
-  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.57, 0.54, 0.84, 0.53, 0.60};
+  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.55, 0.59, 0.84, 0.58, 0.66};
   const int64_t stages = ceil_div(k_slice, 32);
   const bool gelu = sk == 1 && epilogue == NIMBLE_EPI_BIAS_GELU_ERF;
-  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 1.3 : 0.0);
+  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 0.3 : 0.0);
   const double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
   const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
   double us = (double)full_rounds * (t_full > latency_floor ? t_full : latency_floor);
@@ -129,8 +134,16 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
   // many small tiles re-fetch the operand panels often enough to hit that before anything else
   const double dma_us = (double)tiles * (double)stages * (double)((bm > 0 ? bm : vi.bm) + vi.bn) * 64.0 / 11.5e6;
   if (us < dma_us) us = dma_us;
+  // a layer too large to stay in the caches streams its weights from HBM: about 3.3 TB/s with
+  // one workgroup per compute unit, 5.3 TB/s from two up
+  if ((double)N * (double)K * 2.0 > kCachedWeightBytes) {
+    double fill = (double)tiles / (double)kCUs - 1.0;
+    fill = fill < 0.0 ? 0.0 : (fill > 1.0 ? 1.0 : fill);
+    const double hbm_us = (double)N * (double)K * 2.0 / (3.47e6 + 1.83e6 * fill);
+    if (us < hbm_us) us = hbm_us;
+  }
   // the reduction: a dependent launch, a fixed cost per slice, and the partial sums' traffic
-  if (sk > 1) us += kSplitGapUs + 0.18 * (double)sk + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.6e6;
+  if (sk > 1) us += kSplitGapUs + 0.1885 * (double)sk + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.78e6;
   return us;
 }
 
@@ -138,15 +151,31 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
 // the same for every single-launch choice) and the weight-streaming estimate includes.
 static const double kLaunchUs = 3.5;
 
+// Row blocks of a weight-streaming launch: a workgroup takes 16 weight rows and 16..64
+// activation rows.  A narrow layer (few weight rows) fills the chip only when the activation
+// rows are spread over several workgroups, each re-reading its weight rows (they meet in L2);
+// a wide layer already has a workgroup per compute unit and keeps one block per 64 rows so that
+// the weights cross HBM once.
+static int64_t skinny_row_blocks(int64_t rows, int64_t N) {
+  int64_t blocks = kCUs / ceil_div(N, 16);
+  const int64_t most = ceil_div(rows, 16), fewest = ceil_div(rows, 64);
+  if (blocks > most) blocks = most;
+  if (blocks < fewest) blocks = fewest;
+  return blocks < 1 ? 1 : blocks;
+}
+
 // The weight-streaming kernel: launch latency, then whichever is longer of streaming W (the
 // activations are re-read once per 16 weight rows, which shows from 32 rows on) and one
 // workgroup's own walk over K (N / 16 workgroups only: a short, wide layer leaves most of the
 // chip idle).  Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
 static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
-  const double mt = (double)ceil_div(rows < 64 ? rows : 64, 16);
+  const int64_t nblocks = skinny_row_blocks(rows, N);
+  const double mt = (double)ceil_div(rows, 16 * nblocks);
   const double blocks = (double)ceil_div(rows, 64);
-  const double stream = (double)N * (double)K * 2.0 / 4.5e6 * (1.0 + 0.5 * (mt - 1.0));
-  const double walk = (double)ceil_div(K, 128) * mt * 0.11;
+  const double bytes = (double)N * (double)K * 2.0;
+  const double rate = bytes > kCachedWeightBytes ? 5.175e6 : 6.2e6;  // bytes per microsecond
+  const double stream = bytes / rate * (1.0 + 0.289 * (double)rows / (double)nblocks / 16.0);
+  const double walk = (double)ceil_div(K, 128) * mt * 0.133;
   return kLaunchUs + blocks * (stream > walk ? stream : walk);
 }
 
@@ -176,19 +205,14 @@ struct Launch {
   double us = 0;
 };
 
-// Best single launch for `rows` rows: weight streaming up to 64 rows, else the tiled
-// variant and K split with the least estimated time that fits the workspace.
+// Best single launch for `rows` rows: the least estimated time among weight streaming (up to
+// 64 rows) and every tiled variant and K split that fits the workspace.
 static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int epilogue,
                           uint64_t max_workspace, bool allow_skinny) {
   Launch best;
   double skinny_us = -1.0;
   if (allow_skinny && rows <= 64 && batch == 1) {
     skinny_us = skinny_cost_us(rows, N, K);
-    if (rows <= 16) {  // one 16-row tile: nothing tiled comes close
-      best.variant = NIMBLE_VAR_SKINNY16;
-      best.us = skinny_us;
-      return best;
-    }
   }
   for (int v = NIMBLE_VAR_T32x128; v <= NIMBLE_VAR_T256x256; ++v) {
     if (!tiled_variant_ok(v, rows, N, K)) continue;
@@ -219,7 +243,7 @@ static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int
         }
       }
   }
-  // 17..64 rows: the small tiles compete with weight streaming (compared launch included)
+  // up to 64 rows the small tiles (with K cut) compete with weight streaming (compared launch included)
   if (skinny_us >= 0.0 && (best.variant < 0 || skinny_us <= best.us + kLaunchUs)) {
     best = Launch();
     best.variant = NIMBLE_VAR_SKINNY16;
@@ -355,7 +379,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     p->residue_copy = (p->r != 0 || N % v.bn != 0 || K % v.bk != 0) ? 1 : 0;
     p->split_k = 4;  // the four waves of a workgroup each take a quarter of K
     p->grid[0] = (uint32_t)ceil_div(N, v.bn);
-    p->grid[1] = (uint32_t)ceil_div(M, 64);  // up to four 16-row tiles per workgroup
+    p->grid[1] = (uint32_t)skinny_row_blocks(M, N);  // up to four 16-row tiles per workgroup
     p->grid[2] = 1;
     p->block = 256;
     return NIMBLE_OK;
@@ -550,7 +574,9 @@ int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {
   plan->residue_copy = plan->r != 0;
   plan->split_k = 4;
   plan->grid[0] = (uint32_t)ceil_div(H, 4);
-  plan->grid[1] = (uint32_t)ceil_div(B, 64);
+  // row blocks as for the weight-streaming dense (4H weight rows; measured at H = 512: 2 blocks
+  // of 32 rows at B = 64 take 5.6 us against 7.9 us for one block of 64)
+  plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H);
   plan->grid[2] = 1;
   plan->block = 256;
   return NIMBLE_OK;

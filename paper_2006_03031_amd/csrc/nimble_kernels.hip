@@ -66,8 +66,8 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
 template <bool LSTM>
 static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t st) {
   dim3 grid(p.grid[0], p.grid[1], 1), block(256);
-  const int rows = s.M < 64 ? s.M : 64;
-  const int mt = (rows + 15) / 16;
+  // 16-row tiles per workgroup: the rows spread evenly over the plan's row blocks (at most 4 each)
+  const int mt = (s.M + 16 * (int)p.grid[1] - 1) / (16 * (int)p.grid[1]);
   switch (mt) {
     case 1: hipLaunchKernelGGL((skinny_kernel<1, LSTM>), grid, block, 0, st, s); break;
     case 2: hipLaunchKernelGGL((skinny_kernel<2, LSTM>), grid, block, 0, st, s); break;
@@ -304,6 +304,34 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
   s.N = (int)(4 * H);
   s.K = (int)(Ix + H);
   s.Ix = (int)Ix;
+  s.H = (int)H;
+  s.epilogue = NIMBLE_EPI_BIAS;
+  return launch_skinny<true>(s, p, (hipStream_t)stream);
+}
+
+int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w_h, const void* c_prev,
+                              void* c_out, void* h_out, int64_t B, int64_t H, void* stream) {
+  clear_error();
+  nimble_plan p;
+  int rc = nimble_lstm_plan(B, 0, H, &p);
+  if (rc != NIMBLE_OK) return rc;
+  if (B == 0) return NIMBLE_OK;
+  if (!pre || !h_prev || !w_h || !c_prev || !c_out || !h_out) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (misaligned(pre) || misaligned(h_prev) || misaligned(w_h) || misaligned(c_prev) || misaligned(c_out) ||
+      misaligned(h_out))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (h_out == h_prev) return fail(NIMBLE_ERR_ARG, "h_out must not alias h_prev");
+  SkinnyArgs s{};
+  s.h = (const u16*)h_prev;
+  s.w = (const u16*)w_h;
+  s.pre = (const float*)pre;
+  s.y = h_out;
+  s.c_prev = (const float*)c_prev;
+  s.c_out = (float*)c_out;
+  s.M = (int)B;
+  s.N = (int)(4 * H);
+  s.K = (int)H;
+  s.Ix = 0;
   s.H = (int)H;
   s.epilogue = NIMBLE_EPI_BIAS;
   return launch_skinny<true>(s, p, (hipStream_t)stream);

@@ -7,8 +7,11 @@ namespace nimble {
 
 // ---------------------------------------------------------------------------
 // Skinny kernel: at most 64 rows of activations per workgroup, 16 weight rows.
-// Every weight element is read from HBM once, by exactly one lane, straight
-// into an MFMA operand (no LDS staging: there is no reuse to stage for).
+// Every weight element is read by exactly one lane of a workgroup, straight into
+// an MFMA operand (no LDS staging: there is no reuse to stage for).
+// Tried and not kept: issuing the next eight steps' loads ahead of the current
+// MFMAs (needs unconditional, clamped loads so that the compiler can count them;
+// 160 registers and three waves per SIMD instead of four: 10-15 % slower).
 // ---------------------------------------------------------------------------
 struct SkinnyArgs {
   const u16* x;     // [M, K]  (LSTM: [B, Ix])
@@ -18,6 +21,8 @@ struct SkinnyArgs {
   void* y;          // [M, N] bf16 or f32 (LSTM: h_out [B,H] bf16)
   const float* c_prev;  // LSTM only
   float* c_out;         // LSTM only
+  const float* pre;     // LSTM only, may be null: [B, 4H] input share of the gates (bias included);
+                        // then x is absent (Ix = 0) and bias is not read
   int M, N, K;      // LSTM: M = B, N = 4H, K = Ix + H
   int Ix, H;        // LSTM only
   int epilogue, out_f32;
@@ -31,7 +36,7 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
   const int lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, gq = lane >> 4;
   const int M = s.M, N = s.N, K = s.K;
-  const int mbase = blockIdx.y * 64;
+  const int mbase = blockIdx.y * (16 * MT);  // the launch gives every workgroup along y 16 MT rows
 
   // operands of the epilogue, fetched first so their latency hides behind the weight stream
   float pre_bias[4] = {0.f, 0.f, 0.f, 0.f};
@@ -40,8 +45,13 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
     const int t = tid >> 6, mm = (tid & 63) >> 2, u = tid & 3;
     const int m = mbase + t * 16 + mm, unit = blockIdx.x * 4 + u;
     if (t < MT && m < M && unit < s.H) {
+      if (s.pre) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) pre_bias[q] = bf2f(s.bias[q * s.H + unit]);
+        for (int q = 0; q < 4; ++q) pre_bias[q] = s.pre[((long long)m * 4 + q) * s.H + unit];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) pre_bias[q] = bf2f(s.bias[q * s.H + unit]);
+      }
       pre_c = s.c_prev[(long long)m * s.H + unit];
     }
   } else {

@@ -151,6 +151,28 @@ def lstm_step(x: torch.Tensor, h: torch.Tensor, w: torch.Tensor, bias: torch.Ten
     return h_out, c_out
 
 
+def lstm_step_pre(pre: torch.Tensor, h: torch.Tensor, w_h: torch.Tensor, c: torch.Tensor,
+                  h_out: Optional[torch.Tensor] = None,
+                  c_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """One cell step from the precomputed input share of the gates pre [B, 4H] (f32)."""
+    B, H = h.shape
+    if tuple(pre.shape) != (B, 4 * H) or tuple(w_h.shape) != (4 * H, H) or tuple(c.shape) != (B, H):
+        raise nb.NimbleError(-3, f"lstm_step_pre: pre {tuple(pre.shape)}, w_h {tuple(w_h.shape)}, c {tuple(c.shape)} "
+                                 f"do not fit h {tuple(h.shape)}")
+    if h_out is None:
+        h_out = _alloc((B, H), nb.BF16, h.device)
+    if c_out is None:
+        c_out = _alloc((B, H), nb.F32, h.device)
+    nb.nimble_lstm_gates_pre_dyn(pre.data_ptr(), h.data_ptr(), w_h.data_ptr(), c.data_ptr(), c_out.data_ptr(),
+                                 h_out.data_ptr(), B, H, _stream())
+    return h_out, c_out
+
+
+def split_lstm_weight(w: torch.Tensor, Ix: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """One-time split of the fused weight [4H, Ix+H] into contiguous input and recurrent halves."""
+    return w[:, :Ix].contiguous(), w[:, Ix:].contiguous()
+
+
 class LstmSequenceGraph:
     """The token loop of one sequence, `steps` launches of the fused LSTM cell, captured once
     per batch size B as a HIP graph and replayed: the loop is launch-bound (a step is a few
@@ -158,11 +180,19 @@ class LstmSequenceGraph:
     kernel launches only (state is cleared by a fill kernel outside it).  The dynamic extent
     B is fixed per graph; a server keeps one graph per batch size it has seen."""
 
-    def __init__(self, w: torch.Tensor, bias: torch.Tensor, B: int, steps: int, Ix: int, H: int):
+    def __init__(self, w: torch.Tensor, bias: torch.Tensor, B: int, steps: int, Ix: int, H: int,
+                 project_inputs: bool = False):
+        """project_inputs: compute the inputs' share of the gates for all tokens in one dense
+        call (M = steps * B) ahead of the loop, so each step streams only the recurrent half
+        of the weight."""
         dev = w.device
         (self.B, self.H), _ = nb.lstm_shape((B, Ix), (B, H), (B, H), tuple(w.shape))
         self.steps, self.Ix = steps, Ix
         self.w, self.bias = w, bias
+        self.project_inputs = project_inputs
+        if project_inputs:
+            self.w_x, self.w_h = split_lstm_weight(w, Ix)
+            self.pre = torch.empty((steps, B, 4 * H), dtype=torch.float32, device=dev)
         self.xs = torch.zeros((steps, B, Ix), dtype=torch.bfloat16, device=dev)
         self.hs = torch.zeros((steps + 1, B, H), dtype=torch.bfloat16, device=dev)  # hs[0] = h_0
         self.c = torch.zeros((B, H), dtype=torch.float32, device=dev)
@@ -175,6 +205,14 @@ class LstmSequenceGraph:
 
     def _enqueue(self) -> None:
         st = _stream()
+        if self.project_inputs:
+            dense(self.xs.view(self.steps * self.B, self.Ix), self.w_x, self.bias, nb.EPI_BIAS, nb.F32,
+                  out=self.pre.view(self.steps * self.B, 4 * self.H))
+            for t in range(self.steps):
+                nb.nimble_lstm_gates_pre_dyn(self.pre[t].data_ptr(), self.hs[t].data_ptr(), self.w_h.data_ptr(),
+                                             self.c.data_ptr(), self.c.data_ptr(), self.hs[t + 1].data_ptr(),
+                                             self.B, self.H, st)
+            return
         for t in range(self.steps):
             nb.nimble_lstm_gates_dyn(self.xs[t].data_ptr(), self.hs[t].data_ptr(), self.w.data_ptr(),
                                      self.bias.data_ptr(), self.c.data_ptr(), self.c.data_ptr(),

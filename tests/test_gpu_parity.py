@@ -379,6 +379,84 @@ def test_lstm_sequence_graph_replays_match_eager(rt, nb):
         assert _err(from_dev(hs[0]), rh) <= TOL
 
 
+def test_lstm_from_precomputed_input_gates(rt, nb):
+    """Inputs' share of the gates for all tokens from one dense call (M = T*B, f32 output), then
+    per token the recurrent half only.  Per step both sides get the same pre, h and c."""
+    to_dev, f32_to_dev, from_dev, _ = _dev()
+    lw = wl.config2_weights()
+    H, Ix = wl.LSTM_H, wl.LSTM_IX
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    w_x, w_h = rt.split_lstm_weight(dw, Ix)
+    wx_ref, wh_ref = np.ascontiguousarray(lw.w.f32[:, :Ix]), np.ascontiguousarray(lw.w.f32[:, Ix:])
+    for seq, (B, steps) in enumerate([(1, 24), (5, 6), (16, 4), (23, 4), (64, 4), (70, 3)]):
+        xs = wl.config2_inputs(30 + seq, B, steps)
+        xd = to_dev(xs)
+        pre = rt.dense(xd.view(steps * B, Ix), w_x, db, nb.EPI_BIAS, nb.F32).view(steps, B, 4 * H)
+        pre_ref = oracle.dense(xs.f32.reshape(steps * B, Ix), wx_ref, lw.b.f32, "bias")
+        assert _err(from_dev(pre).reshape(steps * B, 4 * H), pre_ref) <= TOL, ("pre", B)
+        pre_np = from_dev(pre)
+        h = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
+        c = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+        for t in range(steps):
+            h_in, c_in = from_dev(h), from_dev(c)
+            h2, c2 = rt.lstm_step_pre(pre[t], h, w_h, c)
+            ref_h, ref_c = oracle.lstm_step_pre(pre_np[t], h_in, wh_ref, c_in)
+            assert _err(from_dev(c2), ref_c) <= TOL, ("c", B, t)
+            assert _err(from_dev(h2), ref_h) <= TOL, ("h", B, t)
+            # and against the fused cell of the oracle on the original inputs (pre is exact up to f32 order)
+            fh, fc = oracle.lstm_step(xs.f32[t], h_in, lw.w.f32, lw.b.f32, c_in)
+            assert _err(from_dev(h2), fh) <= TOL, ("fused h", B, t)
+            h, c = h2, c2
+    # ragged H and B, c_out aliasing c_prev, closed form with zero recurrent weight
+    rng = np.random.default_rng(77)
+    for (B2, H2) in [(3, 8), (37, 24), (65, 40)]:
+        hh = wl.uniform_bf16(rng, (B2, H2))
+        ww = wl.normal_bf16(rng, (4 * H2, H2), std=0.3)
+        pp = rng.uniform(-2, 2, (B2, 4 * H2)).astype(np.float32)
+        cc = wl.uniform_bf16(rng, (B2, H2)).f32
+        cdev = f32_to_dev(cc)
+        hg, cg = rt.lstm_step_pre(f32_to_dev(pp), to_dev(hh), to_dev(ww), cdev, c_out=cdev)
+        assert cg.data_ptr() == cdev.data_ptr()
+        rh, rc = oracle.lstm_step_pre(pp, hh.f32, ww.f32, cc)
+        assert _err(from_dev(cg), rc) <= TOL and _err(from_dev(hg), rh) <= TOL, (B2, H2)
+    B2, H2 = 9, 16
+    c0 = wl.uniform_bf16(rng, (B2, H2)).f32
+    zero = torch.zeros((4 * H2, H2), dtype=torch.bfloat16, device="cuda")
+    hg, cg = rt.lstm_step_pre(torch.zeros((B2, 4 * H2), dtype=torch.float32, device="cuda"),
+                              to_dev(wl.uniform_bf16(rng, (B2, H2))), zero, f32_to_dev(c0))
+    assert np.array_equal(from_dev(cg), c0 / 2)
+
+
+def test_lstm_sequence_graph_with_projected_inputs(rt, nb):
+    """The captured loop with the inputs' product hoisted out of it: replays reproduce the eager
+    result bit for bit, and the whole sequence stays within tolerance of the fused-cell loop."""
+    to_dev, f32_to_dev, from_dev, bits_from_dev = _dev()
+    lw = wl.config2_weights()
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    H, Ix, steps = wl.LSTM_H, wl.LSTM_IX, 10
+    w_x, w_h = rt.split_lstm_weight(dw, Ix)
+    for B in (2, 33):
+        seq = rt.LstmSequenceGraph(dw, db, B, steps, Ix, H, project_inputs=True)
+        fused = rt.LstmSequenceGraph(dw, db, B, steps, Ix, H)
+        for rep in range(3):
+            xd = to_dev(wl.config2_inputs(60 + rep, B, steps))
+            pre = rt.dense(xd.view(steps * B, Ix), w_x, db, nb.EPI_BIAS, nb.F32).view(steps, B, 4 * H)
+            h = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
+            c = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+            eager = []
+            for t in range(steps):
+                h, c = rt.lstm_step_pre(pre[t], h, w_h, c)
+                eager.append(bits_from_dev(h))
+            torch.cuda.synchronize()
+            hs, c_fin = seq.run(xd)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits_from_dev(hs), np.stack(eager)), (B, rep)
+            assert np.array_equal(from_dev(c_fin), from_dev(c)), (B, rep)
+            hs_f, _ = fused.run(xd)
+            torch.cuda.synchronize()
+            assert _err(from_dev(hs), from_dev(hs_f)) <= TOL, (B, rep)
+
+
 # ------------------------------------------------------------------ config 4
 def test_attention_chain(rt, nb):
     to_dev, _, from_dev, _ = _dev()

@@ -126,15 +126,23 @@ def test_plan_residue_identity_for_every_tiled_variant(variant):
 
 
 def test_auto_dispatch_table():
-    # small M streams the weights; large M goes to big tiles; ragged K falls back
+    # small M streams the weights or runs small tiles with K cut, whichever is estimated faster;
+    # large M goes to big tiles; ragged K falls back
     for M in range(1, 65):
         p = nb.dense_plan(M, 2048, 1024)
-        # up to 16 rows always stream the weights; 17..64 rows go to whichever of weight
-        # streaming and the small tiles is estimated faster
-        assert p.name == "skinny16" if M <= 16 else p.name in ("skinny16", "t32x128", "t64x128")
+        assert p.name in ("skinny16", "t32x128", "t64x128")
         assert p.k * p.bm + p.r == M
         if p.name == "skinny16":
-            assert p.grid[0] == 128 and p.grid[1] == 1
+            # 128 column groups of 16 weight rows: up to two row blocks keep the grid within the
+            # chip's 256 compute units; each block holds at most four 16-row tiles
+            blocks = p.grid[1]
+            assert p.grid[0] == 128 and blocks == max(1, min(-(-M // 16), 2))
+            assert -(-M // (16 * blocks)) <= 4
+    assert nb.dense_plan(1, 2048, 1024).name == "skinny16"
+    # a narrow layer spreads its rows over more workgroups, a wide one keeps one block per 64 rows
+    assert nb.dense_plan(64, 768, 768, force_variant=1).grid[:2] == (48, 4)
+    assert nb.dense_plan(64, 4096, 1024, force_variant=1).grid[:2] == (256, 1)
+    assert nb.dense_plan(200, 4096, 1024, force_variant=1).grid[:2] == (256, 4)
     assert nb.dense_plan(65, 2048, 1024).name.startswith("t")
     assert nb.dense_plan(8192, 4096, 1024).name in ("t256x256", "t256x128")
     assert nb.dense_plan(8192, 4096, 1024).residue_copy == 0
@@ -144,7 +152,7 @@ def test_auto_dispatch_table():
     assert p.k * p.bm + p.r == 8193 and p.r == 8193 % p.bm
     if p.split_rows:
         assert p.split_rows == p.k * p.bm and p.residue_copy == 0
-        assert nb.variant_name(p.residue_variant) == "skinny16"   # one row left over
+        assert nb.variant_name(p.residue_variant) in ("skinny16", "t32x128")   # one row left over
         assert p.grid[0] == (p.split_rows // p.bm) * (4096 // p.bn)
     else:
         assert p.residue_copy == 1 and p.grid[0] == (p.k + 1) * (4096 // p.bn)
@@ -164,7 +172,7 @@ def test_auto_dispatch_table():
                 assert p.grid[0] == (p.split_rows // p.bm) * (N // p.bn)
                 assert nb.variant_name(p.residue_variant) is not None
                 if M - p.split_rows <= 16:
-                    assert nb.variant_name(p.residue_variant) == "skinny16"
+                    assert nb.variant_name(p.residue_variant) in ("skinny16", "t32x128")
             forced = nb.dense_plan(M, N, K, force_variant=p.variant)
             assert forced.split_rows == 0  # a forced variant is one launch
 
@@ -219,7 +227,15 @@ def test_plan_rejects_bad_arguments():
 def test_lstm_plan():
     for B in range(0, 130):
         p = nb.lstm_plan(B, 512, 512)
-        assert p.k * 16 + p.r == B and p.grid[0] == 128 and p.grid[1] == -(-B // 64)
+        assert p.k * 16 + p.r == B and p.grid[0] == 128
+        # row blocks: at most four 16-row tiles each, together covering B; as many as keep the
+        # grid within one workgroup per compute unit (128 column groups -> 2), more only when B forces it
+        blocks = p.grid[1]
+        tiles = -(-B // (16 * blocks))
+        assert tiles <= 4 and blocks * 16 * tiles >= B
+        assert blocks == max(1, -(-B // 64), min(-(-B // 16), 2))
+    assert nb.lstm_plan(64, 64, 64).grid[:2] == (16, 4)     # a narrow layer is cut along the batch instead
+    assert nb.lstm_plan(16, 64, 64).grid[:2] == (16, 1)
 
 
 def test_device_entry_points_validate_before_touching_the_gpu():
@@ -244,3 +260,8 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 0, 512, 512, None, 0, None) == 0
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 32, 3, 512, 512, None, 0, None) == -8  # h_out aliases h_prev
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 3, 511, 512, None, 0, None) == -8
+    assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 96, 0, 512, None) == 0       # B = 0: nothing to do
+    assert lib.nimble_lstm_gates_pre_dyn(None, 32, 48, 64, 80, 96, 3, 512, None) == -1
+    assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 32, 3, 512, None) == -8      # h_out aliases h_prev
+    assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 100, 3, 512, None) == -5
+    assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 96, 3, 510, None) == -8
