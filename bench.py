@@ -348,9 +348,66 @@ def config_1_and_3_probe():
     return out
 
 
+def allocation_probe():
+    """Step a3 measured (the memory-planning section's allocation count and latency): outputs of
+    the two FFN calls over the 64 ragged draws allocated per call from torch's caching allocator,
+    against carved out of one storage block sized once for the largest draw."""
+    import torch
+
+    import paper_2006_03031_amd as nb
+    import workloads as wl
+    from paper_2006_03031_amd import runtime as rt
+
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    Ms = [int(m) for m in wl.config5_token_counts()]
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    before = torch.cuda.memory_stats()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        for M in Ms:
+            h = rt._alloc((M, N1), nb.BF16, "cuda")
+            y = rt._alloc((M, N2), nb.BF16, "cuda")
+    t_torch = (time.perf_counter() - t0) / (16 * len(Ms))
+    after = torch.cuda.memory_stats()
+    del h, y
+    arena = rt.StorageArena(max(Ms) * (N1 + N2) * 2 + 4096)
+    mid = torch.cuda.memory_stats()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        for M in Ms:
+            arena.reset()
+            h = arena.alloc((M, N1), nb.BF16)
+            y = arena.alloc((M, N2), nb.BF16)
+    t_arena = (time.perf_counter() - t0) / (16 * len(Ms))
+    end = torch.cuda.memory_stats()
+    key_a, key_s = "allocation.all.allocated", "segment.all.allocated"
+    # the same two allocations made by the bytecode interpreter from its pool (C++, no Python):
+    # alloc_storage + alloc_tensor per output, host nanoseconds from the interpreter's own profile
+    from paper_2006_03031_amd import vm
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    exe = vm.Executable.from_assembler(vm.ffn_block_program(), [_to_dev(w1), _to_dev(b1), _to_dev(w2), _to_dev(b2)])
+    pool = torch.empty(max(Ms) * (N1 + N2) * 2 + (1 << 20), dtype=torch.uint8, device="cuda")
+    x = torch.empty((Ms[0], K1), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+    for _ in range(3):
+        exe.run([x], pool)
+    torch.cuda.synchronize()
+    prof = exe.profile()
+    alloc_ns = sum(prof["opcodes"].get(op, (0, 0))[1] for op in ("AllocStorage", "AllocTensor", "AllocTensorReg"))
+    alloc_n = sum(prof["opcodes"].get(op, (0, 0))[0] for op in ("AllocStorage",))
+    del pool
+    return {"per_output_us_interpreter_pool": round(alloc_ns / max(alloc_n, 1) / 1e3, 3),"per_output_us_caching_allocator": round(t_torch * 1e6, 2), "per_output_us_arena": round(t_arena * 1e6, 2),
+            "allocator_requests_per_step_caching": (after[key_a] - before[key_a]) / (8 * len(Ms)),
+            "allocator_requests_per_step_arena": (end[key_a] - mid[key_a]) / (8 * len(Ms)),
+            "device_segments_caching": after[key_s] - before[key_s],
+            "device_segments_arena": 1 + end[key_s] - mid[key_s]}
+
+
 def _extras():
     out = small_m_probe()
     out.update(config_1_and_3_probe())
+    out["allocation"] = allocation_probe()
     out["achievable"] = achievable_peaks()
     return out
 

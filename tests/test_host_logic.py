@@ -265,3 +265,33 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 32, 3, 512, None) == -8      # h_out aliases h_prev
     assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 100, 3, 512, None) == -5
     assert lib.nimble_lstm_gates_pre_dyn(16, 32, 48, 64, 80, 96, 3, 510, None) == -8
+
+
+def test_storage_arena_offsets_alignment_and_overflow():
+    # storage coalescing (Section 3.3): one block, tensors carved at aligned offsets computed from
+    # the shape function's result; runs on host memory here, the arithmetic is the same
+    torch = pytest.importorskip("torch")
+    from paper_2006_03031_amd import runtime as rt
+    arena = rt.StorageArena(10_000, device="cpu")
+    assert arena.alignment >= nb.storage_alignment() and arena.alignment % 64 == 0
+    a = arena.alloc((3, 5), nb.BF16)       # 30 bytes
+    b = arena.alloc((7,), nb.F32)          # 28 bytes, next aligned offset
+    assert a.dtype == torch.bfloat16 and tuple(a.shape) == (3, 5)
+    assert b.dtype == torch.float32 and tuple(b.shape) == (7,)
+    base = arena.storage.data_ptr() + arena._base_off
+    assert a.data_ptr() == base and a.data_ptr() % arena.alignment == 0
+    assert b.data_ptr() == base + arena.alignment and arena.offset == arena.alignment + 28
+    # the tensors are views of the one storage: writing one does not touch the other
+    a.fill_(1.0)
+    b.fill_(2.0)
+    assert float(a.float().sum()) == 15.0 and float(b.sum()) == 14.0
+    # an empty tensor (M = 0) is a legal allocation of zero bytes
+    z = arena.alloc((0, 4096), nb.BF16)
+    assert z.numel() == 0
+    with pytest.raises(MemoryError):
+        arena.alloc((100, 100), nb.F32)
+    used = arena.offset
+    arena.reset()
+    assert arena.offset == 0 and used > 0
+    c = arena.alloc((3, 5), nb.BF16)
+    assert c.data_ptr() == a.data_ptr()    # the block is reused from the start
