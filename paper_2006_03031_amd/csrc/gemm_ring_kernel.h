@@ -27,12 +27,25 @@ namespace nimble {
 //   MFMA 16x16x32: the A operand is 16 weight rows (n), the B operand 16
 //   activation rows (m); a lane ends up with 4 consecutive n of one row m.
 // ---------------------------------------------------------------------------
-enum { RING_PINGPONG = 1, RING_SOLO = 2 };
+//   RING_WIDE: stages of 64 k instead of 32.  A row then contributes a whole 128-byte line per
+//   stage; with 64-byte pieces every line is asked for twice (once per stage) and the L2s serve
+//   one request per channel and clock whatever its size: all compute units together pulled
+//   13.5-15.5 TB/s into LDS in 64-byte pieces and 22-26 TB/s in whole lines (loads only, no
+//   MFMA), and the 32-wide ring ran within 10 % of the former.  Rows are 8 chunks, chunk c of row
+//   r at slot c ^ ((r >> 1) & 7); S = 2 or 3 slots; one barrier per 64 k, placed between the two
+//   32-wide halves of a stage: by then every wave has issued (and waited for) its last reads of
+//   the slot of stage s, so the slot is refilled with stage s+S, and stage s+1 has landed, whose
+//   first fragments are read during the second half's MFMAs.
+enum { RING_PINGPONG = 1, RING_SOLO = 2, RING_WIDE = 3 };
 
 template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE>
 __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
                                                uint4* smem) {
-  static_assert(S >= 4 || (MODE == RING_SOLO && S == 3), "the pipeline keeps S-2 stages in flight");
+  constexpr bool WIDE = MODE == RING_WIDE;
+  static_assert(WIDE ? (S == 2 || S == 3) : (S >= 4 || (MODE == RING_SOLO && S == 3)),
+                "the pipeline keeps S-2 stages in flight");
+  constexpr int CH = WIDE ? 8 : 4;      // 16-byte chunks per row and stage
+  constexpr int KSH = WIDE ? 6 : 5;     // log2 of the stage width in k
   constexpr int NT = WGM * WGN * 64;
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -41,26 +54,26 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // of passes rounds up: the ring holds BMP rows of A per stage and the extra rows are loaded
   // from the tile's last row (in bounds, never read back), so that every wave issues the same
   // number of loads per stage and one wait count serves them all
-  constexpr int PASS = NT / 4;
+  constexpr int PASS = NT / CH;
   constexpr int A_LD = (BM + PASS - 1) / PASS, B_LD = BN / PASS;
   constexpr int BMP = A_LD * PASS;
   constexpr int LD = A_LD + B_LD;
   static_assert(BN % PASS == 0 && B_LD >= 1, "tile too narrow for the workgroup");
   static_assert(WM % 16 == 0 && WM >= 16, "a wave owns whole 16-row MFMA tiles");
   static_assert(WN % 64 == 0, "the LDS epilogue stages 64-column blocks");
-  static_assert(NW * WM * WN * 2 <= S * (BMP + BN) * 64, "epilogue staging does not fit in the ring");
-  uint4(*As)[BMP * 4] = reinterpret_cast<uint4(*)[BMP * 4]>(smem);
-  uint4(*Bs)[BN * 4] = reinterpret_cast<uint4(*)[BN * 4]>(smem + S * BMP * 4);
+  static_assert(NW * WM * WN * 2 <= S * (BMP + BN) * CH * 16, "epilogue staging does not fit in the ring");
+  uint4(*As)[BMP * CH] = reinterpret_cast<uint4(*)[BMP * CH]>(smem);
+  uint4(*Bs)[BN * CH] = reinterpret_cast<uint4(*)[BN * CH]>(smem + S * BMP * CH);
 
   // gridDim.y > 1: K is cut into gridDim.y slices of whole stages; slice blockIdx.y writes its
   // f32 partial sums to its own [M,N] plane of the output (g.c is then the split-K workspace)
   const int z = blockIdx.z;
-  const int stages_all = g.K >> 5;
+  const int stages_all = g.K >> KSH;
   const int stages_per = (stages_all + (int)gridDim.y - 1) / (int)gridDim.y;
   const int stage0 = (int)blockIdx.y * stages_per;
   const int KS = (stages_all - stage0) < stages_per ? (stages_all - stage0) : stages_per;
-  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa + (stage0 << 5);
-  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb + (stage0 << 5);
+  const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa + (stage0 << KSH);
+  const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb + (stage0 << KSH);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
@@ -68,8 +81,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // Address = uniform base of (tile row 0, pass i, stage k0) + per-lane byte offset.
   // MEDGE (the last tile along M when r != 0): rows past M-1 are fetched from row M-1, so
   // every load stays in bounds; their products land in rows the epilogue never stores.
-  const int ld_row = tid >> 2;
-  const int ld_c = (tid & 3) ^ ((ld_row >> 1) & 3);
+  const int ld_row = tid / CH;
+  const int ld_c = (tid & (CH - 1)) ^ ((ld_row >> 1) & (CH - 1));
   uint32_t a_off[A_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
@@ -85,21 +98,22 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&As[0][wave * 64]));
   const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(&Bs[0][wave * 64]));
   auto dma = [&](int ks, int slot) {
-    const int k0 = ks << 5;
+    const int k0 = ks << KSH;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BMP * 64) + i * NT * 16);
+      dma16_so(a_off[i], a_base + k0, a_dst + slot * (BMP * CH * 16) + i * NT * 16);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      dma16_so(b_off, b_base + i * b_pass + k0, b_dst + slot * (BN * 64) + i * NT * 16);
+      dma16_so(b_off, b_base + i * b_pass + k0, b_dst + slot * (BN * CH * 16) + i * NT * 16);
   };
 
   // fragment reads: lane -> row (lane & 15), logical chunk (lane >> 4)
   const int fr_row = lane & 15;
   const int fr_q = lane >> 4;
-  const int fr_phys = fr_q ^ ((fr_row >> 1) & 3);
-  const int fr_a = (wm * WM + fr_row) * 4 + fr_phys;
-  const int fr_b = (wn * WN + fr_row) * 4 + fr_phys;
+  // (rows 16 apart share the swizzle term; the wide ring's second half adds 4 to the logical chunk)
+  const int fr_phys = fr_q ^ ((fr_row >> 1) & (CH - 1));
+  const int fr_a = (wm * WM + fr_row) * CH + fr_phys;
+  const int fr_b = (wn * WN + fr_row) * CH + fr_phys;
 
   f32x4 acc[TN][TM];
 #pragma unroll
@@ -112,8 +126,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // volatile statement before the first ring load: the wait for stage 0 below then covers it
   // (loads complete in order), and the compiler's own wait counting never sees it.  The 288- and
   // 320-row tiles leave no LDS for it and load the bias in the epilogue.
-  constexpr bool BIAS_LDS = S * (BMP + BN) * 64 + BN * 2 <= 160 * 1024;
-  u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * 4);
+  constexpr bool BIAS_LDS = S * (BMP + BN) * CH * 16 + BN * 2 <= 160 * 1024;
+  u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * CH);
   const bool park_bias = BIAS_LDS && g.epilogue != NIMBLE_EPI_NONE && !g.out_f32;
   uint2 bias_pre;
   if (park_bias) {  // uniform branch; every lane loads (lanes past BN/4 repeat an earlier lane's 8 bytes)
@@ -121,18 +135,23 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(bias_pre) : "v"(src) : "memory");
   }
 
+  if constexpr (WIDE) {
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s) {
-    if constexpr (MODE == RING_SOLO)
-      dma(s < KS ? s : KS - 1, s);  // always S-1 stages in flight (see the stage code below)
-    else if (s < KS)
-      dma(s, s);
+    for (int s = 0; s < S; ++s) dma(s < KS ? s : KS - 1, s);  // always S stages in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * LD) : "memory");  // stage 0 landed
+  } else {
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) {
+      if constexpr (MODE == RING_SOLO)
+        dma(s < KS ? s : KS - 1, s);  // always S-1 stages in flight (see the stage code below)
+      else if (s < KS)
+        dma(s, s);
+    }
+    if (MODE == RING_SOLO || KS - 1 >= S - 2)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
+    else
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
-
-  if (MODE == RING_SOLO || KS - 1 >= S - 2)
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");  // stage 0 landed
-  else
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (park_bias && tid < BN / 4) *(uint2*)(bias_lds + tid * 4) = bias_pre;  // read after the epilogue's barrier
 
@@ -242,6 +261,50 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     // the MFMAs above are opaque to the compiler's hazard handling: let the last results land
     // before anything reads the accumulators
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  } else if constexpr (MODE == RING_WIDE) {
+    // Same straight-line schedule as above on stages of 64 k: two halves of 32 k per stage, the
+    // fragments of the next half read into the other register set in between the MFMAs of the
+    // current one, one barrier per stage.
+    bf16x8 xa[2][TM], wb[2][TN];
+    const uint4* a_rd = &As[0][fr_a];
+    const uint4* b_rd = &Bs[0][fr_b];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) xa[0][j] = as_bf16x8(a_rd[j * 16 * CH]);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(b_rd[i * 16 * CH]);
+    // reads of the other half of a row: logical chunk + 4, i.e. physical chunk ^ 4
+    const int half = ((fr_phys ^ 4) - fr_phys);
+    auto half_step = [&](const uint4* a_nx, const uint4* b_nx, auto cur_tag) {
+      constexpr int CUR = decltype(cur_tag)::value;
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+        wb[CUR ^ 1][i] = as_bf16x8(b_nx[i * 16 * CH]);
+#pragma unroll
+        for (int x = i * TM / TN; x < (i + 1) * TM / TN; ++x) xa[CUR ^ 1][x] = as_bf16x8(a_nx[x * 16 * CH]);
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < TM; ++j) mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+      }
+    };
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
+    int slot = 0;
+    for (int ks = 0; ks < KS; ++ks) {
+      // first half: multiply k 0..31 of stage ks, read its k 32..63
+      half_step(a_rd + slot * (BMP * CH) + half, b_rd + slot * (BN * CH) + half, T0{});
+      // every read of this stage's slot has been issued; once they have returned and every wave
+      // is here the slot can be refilled, and stage ks+1 has landed when only the S-2 younger
+      // stages are in flight
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+      __syncthreads();
+      const int ld = ks + S;
+      dma(ld < KS ? ld : KS - 1, slot);  // past the end of K: the last stage again, never read
+      slot = slot + 1 == S ? 0 : slot + 1;
+      // second half: multiply k 32..63 of stage ks, read k 0..31 of stage ks+1
+      half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{});
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
   }
 
   // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
@@ -323,36 +386,39 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 // the 8-wave ping-pong, slower at whole rounds, so that shape is not built.
 // BM may be any multiple of 16 * WGM: the 256-wide tile is built at 128..256 rows so that the
 // dispatch function can pick the height at which the run-time M fills whole rounds of the chip.
-template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4>
+template <int BM, int BN, int WGM, int WGN, bool RESIDUE, int S = 4, bool WIDE = false>
 __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     gemm_ring_kernel(GemmArgs g, int tiles_m, int tiles_n, int group_m) {
-  // the straight-line schedule with two fragment sets wherever accumulators and both sets fit in
-  // a wave's 256 registers (wave tiles up to 128 rows by 64 columns); the two-group ping-pong
-  // with one set for the 288- and 320-row heights of the 256-wide tile
-  constexpr int kPingPong = WGM == 2 && WGN == 4 && BM > 256 ? RING_PINGPONG : RING_SOLO;
-  constexpr int kPass = WGM * WGN * 16;  // rows per load pass: the ring holds whole passes of A
+  // WIDE: stages of 64 k (K must be a multiple of 64; the launcher sees to that), S = 2 or 3.
+  // Else stages of 32 k: the straight-line schedule with two fragment sets wherever accumulators
+  // and both sets fit in a wave's 256 registers (wave tiles up to 128 rows by 64 columns); the
+  // two-group ping-pong with one set for the 288- and 320-row heights of the 256-wide tile
+  constexpr int kMode = WIDE ? RING_WIDE : (WGM == 2 && WGN == 4 && BM > 256 ? RING_PINGPONG : RING_SOLO);
+  constexpr int kCh = WIDE ? 8 : 4;
+  constexpr int kPass = WGM * WGN * 64 / kCh;  // rows per load pass: the ring holds whole passes of A
   constexpr int kBmp = (BM + kPass - 1) / kPass * kPass;
   // the ring (which also holds the masked body's two 64-wide tiles), then BN bias values where they fit
-  constexpr int kRing = S * (kBmp + BN) * 4;
+  constexpr int kRing = S * (kBmp + BN) * kCh;
+  static_assert(kRing >= 2 * (BM + BN) * 8, "the masked body needs two 64-wide tiles");
   constexpr int kBias = kRing * 16 + BN * 2 <= 160 * 1024 ? BN / 8 : 0;
   __shared__ __attribute__((aligned(16))) uint4 smem[kRing + kBias];
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   if (RESIDUE) {
-    // the packed epilogue needs 16-byte aligned output rows; K must be whole 32-wide stages
-    const bool ragged = (n0 + BN > g.N) || ((g.K & 31) != 0) || ((g.ldc & 7) != 0);
+    // the packed epilogue needs 16-byte aligned output rows; K must be whole stages
+    const bool ragged = (n0 + BN > g.N) || ((g.K & (WIDE ? 63 : 31)) != 0) || ((g.ldc & 7) != 0);
     if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
       // (the reduced tile heights are only dispatched to shapes without ragged N or K)
       if constexpr (BM % 128 == 0 || BN == 128) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
       return;
     }
     if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
-      gemm_ring_body<BM, BN, WGM, WGN, S, true, kPingPong>(g, m0, n0, smem);
+      gemm_ring_body<BM, BN, WGM, WGN, S, true, kMode>(g, m0, n0, smem);
       return;
     }
   }
-  gemm_ring_body<BM, BN, WGM, WGN, S, false, kPingPong>(g, m0, n0, smem);
+  gemm_ring_body<BM, BN, WGM, WGN, S, false, kMode>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------

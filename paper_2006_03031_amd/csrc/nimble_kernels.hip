@@ -44,7 +44,9 @@ static int check_hip(hipError_t e, const char* what) {
   return fail(NIMBLE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-template <int BM, int BN, int WGM, int WGN, int S = 4>
+// WS: slots of the 64-wide ring (0: the tile is only built on the 32-wide ring).  The 64-wide
+// ring runs whenever K is whole 64-wide stages and every K slice gets at least one of them.
+template <int BM, int BN, int WGM, int WGN, int WS = 2, int S = 4>
 static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   int group_m = 4;  // measured best of 1..32 on the BERT-large FFN shapes
@@ -53,7 +55,21 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
     if (v > 0) group_m = v;
   }
   if (group_m > tiles_m) group_m = tiles_m;
-  dim3 grid(p.grid[0], p.split_k > 1 ? p.split_k : 1, p.grid[2]), block(WGM * WGN * 64);
+  const int slices = p.split_k > 1 ? p.split_k : 1;
+  dim3 grid(p.grid[0], slices, p.grid[2]), block(WGM * WGN * 64);
+  if constexpr (WS > 0) {
+    static const bool ring32_only = std::getenv("NIMBLE_RING32") != nullptr;  // measurement knob
+    const int stages = g.K >> 6, per = (stages + slices - 1) / slices;
+    if (!ring32_only && g.K > 0 && (g.K & 63) == 0 && per * (slices - 1) < stages) {
+      if (p.residue_copy)
+        hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true, WS, true>), grid, block, 0, st, g, tiles_m,
+                           tiles_n, group_m);
+      else
+        hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, false, WS, true>), grid, block, 0, st, g, tiles_m,
+                           tiles_n, group_m);
+      return check_hip(hipGetLastError(), "ring kernel launch");
+    }
+  }
   if (p.residue_copy)
     hipLaunchKernelGGL((gemm_ring_kernel<BM, BN, WGM, WGN, true, S>), grid, block, 0, st, g, tiles_m,
                        tiles_n, group_m);
@@ -97,15 +113,15 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
       s.out_f32 = g.out_f32;
       return launch_skinny<false>(s, p, st);
     }
-    case NIMBLE_VAR_T32x128: return launch_ring<32, 128, 1, 2>(g, p, st);
-    case NIMBLE_VAR_T64x128: return launch_ring<64, 128, 2, 2>(g, p, st);
+    case NIMBLE_VAR_T32x128: return launch_ring<32, 128, 1, 2, 3>(g, p, st);
+    case NIMBLE_VAR_T64x128: return launch_ring<64, 128, 2, 2, 3>(g, p, st);
     case NIMBLE_VAR_T128x128: return launch_ring<128, 128, 2, 2>(g, p, st);
     case NIMBLE_VAR_T256x128:
-      return launch_ring<256, 128, 4, 2>(g, p, st);
+      return launch_ring<256, 128, 4, 2, 3>(g, p, st);
     case NIMBLE_VAR_T256x256:
       switch (p.bm) {  // the tile height the dispatch function chose for this M
-        case 320: return launch_ring<320, 256, 2, 4>(g, p, st);
-        case 288: return launch_ring<288, 256, 2, 4>(g, p, st);
+        case 320: return launch_ring<320, 256, 2, 4, 0>(g, p, st);
+        case 288: return launch_ring<288, 256, 2, 4, 0>(g, p, st);
         case 256: return launch_ring<256, 256, 2, 4>(g, p, st);
         case 224: return launch_ring<224, 256, 2, 4>(g, p, st);
         case 192: return launch_ring<192, 256, 2, 4>(g, p, st);
