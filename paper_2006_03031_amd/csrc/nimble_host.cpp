@@ -50,18 +50,18 @@ static const int64_t kCUs = 256;
 static double tile_cost(int variant, int64_t K, int epilogue, int bm = 0) {
   double eff;
   switch (variant) {
-    case NIMBLE_VAR_T32x128: eff = 0.394; break;
-    case NIMBLE_VAR_T64x128: eff = 0.527; break;
-    case NIMBLE_VAR_T128x128: eff = 0.817; break;
-    case NIMBLE_VAR_T256x128: eff = 0.848; break;
-    case NIMBLE_VAR_T256x256: eff = 1.05; break;
+    case NIMBLE_VAR_T32x128: eff = 0.236; break;
+    case NIMBLE_VAR_T64x128: eff = 0.474; break;
+    case NIMBLE_VAR_T128x128: eff = 0.589; break;
+    case NIMBLE_VAR_T256x128: eff = 0.982; break;
+    case NIMBLE_VAR_T256x256: eff = 1.10; break;
     default: return 1e30;
   }
   const double k0 = (epilogue == NIMBLE_EPI_BIAS_GELU_ERF) ? 256.0 : 128.0;
   // a tile of another height loads the same weight panel for fewer or more rows: measured
-  // time(bm) / time(256) = 0.16 + 0.84 bm/256 for the 256-wide tile (bm = 128..320)
+  // time(bm) / time(256) = 0.13 + 0.87 bm/256 for the 256-wide tile (bm = 128..320)
   const double height = (bm > 0 && bm != kVariants[variant].bm)
-                            ? 0.158 + 0.842 * (double)bm / (double)kVariants[variant].bm : 1.0;
+                            ? 0.1325 + 0.8675 * (double)bm / (double)kVariants[variant].bm : 1.0;
   return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) * height / eff;
 }
 
@@ -92,12 +92,15 @@ static const double kUsPerUnit = 4.4e-7;
 static const double kLaunchGapUs = 3.5;
 // The same gap as it shows between a K-split kernel and its reduction, whose launch the
 // hardware queue has already decoded while the first kernel runs.
-static const double kSplitGapUs = 1.44;
+static const double kSplitGapUs = 1.65;
 
 // Weights above this size are taken to come from HBM on every call (the L2s hold 32 MB, the
 // memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
 // as cache-resident, which is what a layer loop or a token loop sees.
 static const double kCachedWeightBytes = 64e6;
+
+// Workgroups of a variant that share a compute unit (LDS and registers permitting).
+static const int kTilesPerCU[NIMBLE_VAR_COUNT] = {1, 1, 2, 2, 2, 1, 1};
 
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
@@ -116,34 +119,36 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
   // a workgroup cannot go faster than its loads arrive through the direct global->LDS path:
   // a 32-wide stage of (bm + bn) rows costs a lone workgroup 0.13 .. 0.3 us.  A GELU epilogue
   // adds about a microsecond to such a latency-bound tile.
-  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.181, 0.104, 0.21, 0.315, 0.30};
+  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.146, 0.161, 0.321, 0.339, 0.30};
   // time of a tile in a nearly empty last round relative to a full one
-  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.55, 0.59, 0.84, 0.58, 0.66};
+  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.20, 0.43, 0.84, 0.67, 0.73};
   const int64_t stages = ceil_div(k_slice, 32);
   const bool gelu = sk == 1 && epilogue == NIMBLE_EPI_BIAS_GELU_ERF;
-  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 0.3 : 0.0);
+  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 0.94 : 0.0);
   const double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
-  const int64_t full_rounds = tiles / kCUs, rem = tiles % kCUs;
+  // a round is one tile per compute unit for the 8-wave tiles, two for the smaller ones
+  const int64_t slots = kCUs * kTilesPerCU[v];
+  const int64_t full_rounds = tiles / slots, rem = tiles % slots;
   double us = (double)full_rounds * (t_full > latency_floor ? t_full : latency_floor);
   if (rem > 0) {
-    const double occ = (double)rem / (double)kCUs;
+    const double occ = (double)rem / (double)slots;
     const double t_part = t_full * (kLoneTile[v] + (1.0 - kLoneTile[v]) * occ);
     us += t_part > latency_floor ? t_part : latency_floor;
   }
-  // all workgroups together pull about 11.5 TB/s from the L2s into LDS with real operand data:
+  // all workgroups together pull about 14 TB/s from the L2s into LDS with real operand data:
   // many small tiles re-fetch the operand panels often enough to hit that before anything else
-  const double dma_us = (double)tiles * (double)stages * (double)((bm > 0 ? bm : vi.bm) + vi.bn) * 64.0 / 11.5e6;
+  const double dma_us = (double)tiles * (double)stages * (double)((bm > 0 ? bm : vi.bm) + vi.bn) * 64.0 / 13.9e6;
   if (us < dma_us) us = dma_us;
-  // a layer too large to stay in the caches streams its weights from HBM: about 3.3 TB/s with
-  // one workgroup per compute unit, 5.3 TB/s from two up
+  // a layer too large to stay in the caches streams its weights from HBM: about 4.2 TB/s with
+  // one workgroup per compute unit, 6.4 TB/s from two up
   if ((double)N * (double)K * 2.0 > kCachedWeightBytes) {
     double fill = (double)tiles / (double)kCUs - 1.0;
     fill = fill < 0.0 ? 0.0 : (fill > 1.0 ? 1.0 : fill);
-    const double hbm_us = (double)N * (double)K * 2.0 / (3.47e6 + 1.83e6 * fill);
+    const double hbm_us = (double)N * (double)K * 2.0 / (4.19e6 + 2.21e6 * fill);
     if (us < hbm_us) us = hbm_us;
   }
   // the reduction: a dependent launch, a fixed cost per slice, and the partial sums' traffic
-  if (sk > 1) us += kSplitGapUs + 0.1885 * (double)sk + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.78e6;
+  if (sk > 1) us += kSplitGapUs + 0.259 * (double)sk + (double)(sk + 1) * (double)rows * (double)N * 4.0 / 3.97e6;
   return us;
 }
 
@@ -173,9 +178,9 @@ static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
   const double mt = (double)ceil_div(rows, 16 * nblocks);
   const double blocks = (double)ceil_div(rows, 64);
   const double bytes = (double)N * (double)K * 2.0;
-  const double rate = bytes > kCachedWeightBytes ? 5.175e6 : 6.2e6;  // bytes per microsecond
-  const double stream = bytes / rate * (1.0 + 0.289 * (double)rows / (double)nblocks / 16.0);
-  const double walk = (double)ceil_div(K, 128) * mt * 0.133;
+  const double rate = bytes > kCachedWeightBytes ? 5.94e6 : 7.15e6;  // bytes per microsecond
+  const double stream = bytes / rate * (1.0 + 0.553 * (double)rows / (double)nblocks / 16.0);
+  const double walk = (double)ceil_div(K, 128) * mt * 0.126;
   return kLaunchUs + blocks * (stream > walk ? stream : walk);
 }
 
@@ -326,8 +331,9 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
           if (N % vi.bn != 0 || K % vi.bk != 0) continue;
           const int64_t tiles_n = N / vi.bn;
           int64_t cuts[2] = {(M / vi.bm) * vi.bm, 0};
-          if (kCUs % tiles_n == 0) {
-            const int64_t rows_per_round = (kCUs / tiles_n) * vi.bm;
+          const int64_t slots = kCUs * kTilesPerCU[v];
+          if (slots % tiles_n == 0) {
+            const int64_t rows_per_round = (slots / tiles_n) * vi.bm;
             cuts[1] = (M / rows_per_round) * rows_per_round;
           }
           for (int c = 0; c < 2; ++c) {
