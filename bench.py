@@ -404,10 +404,54 @@ def allocation_probe():
             "device_segments_arena": 1 + end[key_s] - mid[key_s]}
 
 
+def two_requests_in_flight(steps: int = 256, warmup: int = 64):
+    """The headline workload with two requests in flight on two streams (alternate draws, each
+    stream with its own arena and K-split workspace): kernels of one request fill the launch
+    gaps, partial last rounds and output-write phases of the other.  Reported beside the
+    headline, which stays one request at a time on one stream."""
+    import torch
+
+    import paper_2006_03031_amd as nb
+    import workloads as wl
+    from paper_2006_03031_amd import runtime as rt
+
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    epi = {"bias": nb.EPI_BIAS, "bias_gelu": nb.EPI_BIAS_GELU_ERF}
+    Ms = [int(m) for m in wl.config5_token_counts()]
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    dw1, db1, dw2, db2 = _to_dev(w1), _to_dev(b1), _to_dev(w2), _to_dev(b2)
+    x_all = _to_dev(wl.activations(5, 0, max(Ms), K1))
+    streams = [torch.cuda.Stream() for _ in range(2)]   # default priority
+    arenas = [rt.StorageArena(max(Ms) * (N1 + N2) * 2 + 4096) for _ in range(2)]
+    spaces = [torch.empty(rt.WORKSPACE_BYTES, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+
+    def step(i):
+        s = i & 1
+        with torch.cuda.stream(streams[s]):
+            M = Ms[i % len(Ms)]
+            arenas[s].reset()
+            h = rt.dense(x_all[:M], dw1, db1, epi[e1], arena=arenas[s], workspace=spaces[s])
+            rt.dense(h, dw2, db2, epi[e2], arena=arenas[s], workspace=spaces[s])
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    t = time.perf_counter() - t0
+    flops = sum(2.0 * Ms[i % len(Ms)] * (N1 * K1 + N2 * K2) for i in range(steps))
+    return {"TFLOPs": round(flops / t / 1e12, 1), "ms_per_step": round(t / steps * 1e3, 4), "steps": steps}
+
+
 def _extras():
     out = small_m_probe()
     out.update(config_1_and_3_probe())
     out["allocation"] = allocation_probe()
+    out["two_requests_in_flight"] = two_requests_in_flight()
     out["achievable"] = achievable_peaks()
     return out
 
