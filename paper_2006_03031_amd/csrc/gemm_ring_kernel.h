@@ -402,23 +402,32 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
   static_assert(kRing >= 2 * (BM + BN) * 8, "the masked body needs two 64-wide tiles");
   constexpr int kBias = kRing * 16 + BN * 2 <= 160 * 1024 ? BN / 8 : 0;
   __shared__ __attribute__((aligned(16))) uint4 smem[kRing + kBias];
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  if (RESIDUE) {
-    // the packed epilogue needs 16-byte aligned output rows; K must be whole stages
-    const bool ragged = (n0 + BN > g.N) || ((g.K & (WIDE ? 63 : 31)) != 0) || ((g.ldc & 7) != 0);
-    if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
-      // (the reduced tile heights are only dispatched to shapes without ragged N or K)
-      if constexpr (BM % 128 == 0 || BN == 128) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
-      return;
+  // A workgroup walks the tiles blockIdx.x, blockIdx.x + gridDim.x, ...: the launcher starts at most
+  // as many workgroups as the chip holds at once, so a launch of several rounds pays the 2-3 us it
+  // takes to retire a workgroup and start the next one on its compute unit only once.  (gridDim.x
+  // is a multiple of 8 whenever a workgroup gets more than one tile, so a workgroup's tiles stay in
+  // the run of tile ids of its own XCD.)
+  const int tiles_total = tiles_m * tiles_n;
+  for (int t = blockIdx.x; t < tiles_total; t += gridDim.x) {
+    if (t != (int)blockIdx.x) __syncthreads();  // the previous tile's epilogue is done with the LDS
+    int tile_m, tile_n;
+    tile_of_block(t, tiles_total, tiles_m, tiles_n, group_m, tile_m, tile_n);
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    if (RESIDUE) {
+      // the packed epilogue needs 16-byte aligned output rows; K must be whole stages
+      const bool ragged = (n0 + BN > g.N) || ((g.K & (WIDE ? 63 : 31)) != 0) || ((g.ldc & 7) != 0);
+      if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
+        // (the reduced tile heights are only dispatched to shapes without ragged N or K)
+        if constexpr (BM % 128 == 0 || BN == 128) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+        continue;
+      }
+      if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
+        gemm_ring_body<BM, BN, WGM, WGN, S, true, kMode>(g, m0, n0, smem);
+        continue;
+      }
     }
-    if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
-      gemm_ring_body<BM, BN, WGM, WGN, S, true, kMode>(g, m0, n0, smem);
-      return;
-    }
+    gemm_ring_body<BM, BN, WGM, WGN, S, false, kMode>(g, m0, n0, smem);
   }
-  gemm_ring_body<BM, BN, WGM, WGN, S, false, kMode>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------

@@ -56,7 +56,15 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   }
   if (group_m > tiles_m) group_m = tiles_m;
   const int slices = p.split_k > 1 ? p.split_k : 1;
-  dim3 grid(p.grid[0], slices, p.grid[2]), block(WGM * WGN * 64);
+  // at most as many workgroups as are resident at once (one per compute unit for the 8-wave
+  // tiles, two for the smaller ones); each walks its share of the tiles
+  unsigned wgs = p.grid[0];
+  {
+    static const bool one_tile_each = std::getenv("NIMBLE_NO_PERSIST") != nullptr;  // measurement knob
+    const unsigned resident = 256u * (WGM * WGN <= 4 ? 2u : 1u);
+    if (!one_tile_each && slices == 1 && p.grid[2] == 1 && wgs > resident) wgs = resident;
+  }
+  dim3 grid(wgs, slices, p.grid[2]), block(WGM * WGN * 64);
   if constexpr (WS > 0) {
     static const bool ring32_only = std::getenv("NIMBLE_RING32") != nullptr;  // measurement knob
     const int stages = g.K >> 6, per = (stages + slices - 1) / slices;
