@@ -209,6 +209,31 @@ def test_row_prefix_invariance_on_gpu(rt, nb):
             assert np.array_equal(part, full[:M])
 
 
+def test_two_requests_in_flight_on_two_streams(rt, nb):
+    """Dense calls of two requests interleaved on two streams, each with its own K-split workspace
+    (calls that overlap must not share one): every output matches the same call made alone."""
+    to_dev, _, from_dev, bits_from_dev = _dev()
+    rng = np.random.default_rng(31)
+    N, K = 768, 3072   # K-split plans at these M
+    w, b = wl.normal_bf16(rng, (N, K)), wl.uniform_bf16(rng, (N,))
+    wd, bd = to_dev(w), to_dev(b)
+    Ms = [40, 130, 257, 512, 96, 300]
+    xs = [to_dev(wl.uniform_bf16(rng, (M, K))) for M in Ms]
+    alone = [bits_from_dev(rt.dense(x, wd, bd, nb.EPI_BIAS)) for x in xs]
+    assert any(nb.dense_plan(M, N, K).split_k > 1 for M in Ms)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    spaces = [torch.empty(rt.WORKSPACE_BYTES, dtype=torch.uint8, device="cuda") for _ in streams]
+    for rep in range(3):
+        outs = []
+        for i, x in enumerate(xs):
+            with torch.cuda.stream(streams[i & 1]):
+                outs.append(rt.dense(x, wd, bd, nb.EPI_BIAS, workspace=spaces[i & 1]))
+        torch.cuda.synchronize()
+        for i, y in enumerate(outs):
+            assert np.array_equal(bits_from_dev(y), alone[i]), (rep, Ms[i])
+
+
 # ------------------------------------------------------------------ config 3
 def test_config3_bert_base_gemms(rt, nb):
     to_dev, _, from_dev, _ = _dev()
