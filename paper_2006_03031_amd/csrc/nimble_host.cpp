@@ -40,7 +40,7 @@ const VariantInfo kVariants[NIMBLE_VAR_COUNT] = {
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Number of compute units of one MI355X.
-static const int64_t kCUs = 256;
+static const int64_t kCUs = kComputeUnits;
 
 // Estimated time of one macro tile, in arbitrary units: the tile's area times
 // (K plus a fixed per-tile overhead expressed in units of K: pipeline fill and
@@ -98,9 +98,6 @@ static const double kSplitGapUs = 1.65;
 // memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
 // as cache-resident, which is what a layer loop or a token loop sees.
 static const double kCachedWeightBytes = 64e6;
-
-// Workgroups of a variant that share a compute unit (LDS and registers permitting).
-static const int kTilesPerCU[NIMBLE_VAR_COUNT] = {1, 1, 2, 2, 2, 1, 1};
 
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs

@@ -12,6 +12,11 @@ struct VariantInfo {
 };
 extern const VariantInfo kVariants[NIMBLE_VAR_COUNT];
 
+// The chip this library is written for: MI355X, 256 compute units in 8 XCDs.
+constexpr int kComputeUnits = 256;
+// Workgroups of a tiled variant that share a compute unit (LDS and registers permitting).
+constexpr int kTilesPerCU[NIMBLE_VAR_COUNT] = {1, 1, 2, 2, 2, 1, 1};
+
 // Record a message for nimble_last_error() and return `code`.
 int fail(int code, const char* fmt, ...);
 void clear_error();

@@ -61,7 +61,7 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   unsigned wgs = p.grid[0];
   {
     static const bool one_tile_each = std::getenv("NIMBLE_NO_PERSIST") != nullptr;  // measurement knob
-    const unsigned resident = 256u * (WGM * WGN <= 4 ? 2u : 1u);
+    const unsigned resident = (unsigned)(kComputeUnits * kTilesPerCU[p.variant]);
     if (!one_tile_each && slices == 1 && p.grid[2] == 1 && wgs > resident) wgs = resident;
   }
   dim3 grid(wgs, slices, p.grid[2]), block(WGM * WGN * 64);
