@@ -136,6 +136,45 @@ def test_ring_variants_short_and_odd_stage_counts(rt, nb, variant):
         _sweep(rt, nb, variant, N=bn, K=K, Ms=[bm, bm + 5, 2 * bm], epilogue="bias")
 
 
+@pytest.mark.parametrize("variant", sorted(TILED))
+def test_tile_walk_more_tiles_than_resident_workgroups(rt, nb, variant):
+    """Launches with more tiles than workgroups resident at once (256 for the 8-wave tiles, 512 for
+    the smaller ones): every workgroup walks several tiles, ragged last tile row and ragged N
+    included, on both ring widths (K = 192 is whole 64-wide stages, K = 160 is not)."""
+    bm, bn = TILED[variant]
+    resident = 512 if bm <= 128 and bn == 128 else 256
+    tiles_n = 5 if bn == 128 else 3
+    rows = (2 * resident // tiles_n + 3) * bm + 1     # > 2 tiles per workgroup, r = 1
+    assert -(-rows // bm) * tiles_n > 2 * resident
+    for K in (192, 160):
+        _sweep(rt, nb, variant, N=tiles_n * bn, K=K, Ms=[rows], epilogue="bias_gelu", seed=variant)
+    _sweep(rt, nb, variant, N=tiles_n * bn - 24, K=64, Ms=[rows - 1], epilogue="bias", seed=variant)
+
+
+def test_random_shapes_through_the_dispatch_function(rt, nb):
+    """Seeded random (M, N, K, epilogue, output type) through the automatic dispatch: whatever it
+    picks (weight streaming, any tile, K split, row split) must agree with the oracle."""
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(2006)
+    seen = set()
+    for case in range(48):
+        M = int(rng.choice([rng.integers(1, 65), rng.integers(65, 700), rng.integers(700, 2600)]))
+        N = int(rng.choice([rng.integers(1, 40) * 8, rng.integers(1, 9) * 128, rng.integers(4, 10) * 256]))
+        K = int(rng.choice([rng.integers(1, 40) * 8, rng.integers(1, 24) * 64, rng.integers(1, 12) * 32]))
+        epi = ["none", "bias", "bias_gelu"][int(rng.integers(0, 3))]
+        out_dtype = int(rng.integers(0, 2))
+        while M * N * K > 6e8:
+            M = max(1, M // 2)
+        x, w, b = wl.uniform_bf16(rng, (M, K)), wl.normal_bf16(rng, (N, K), std=0.05), wl.uniform_bf16(rng, (N,))
+        p = nb.dense_plan(M, N, K, EPI[epi], out_dtype)
+        seen.add((p.name, p.split_k > 1 and p.variant > 1, p.split_rows > 0))
+        y = rt.dense(to_dev(x), to_dev(w), to_dev(b) if epi != "none" else None, EPI[epi], out_dtype)
+        ref = oracle.dense(x.f32, w.f32, b.f32 if epi != "none" else None, epi)
+        assert tuple(y.shape) == (M, N)
+        assert _err(from_dev(y), ref) <= TOL, (case, M, N, K, epi, out_dtype, p.name, p.split_k)
+    assert len({name for name, _, _ in seen}) >= 4, seen   # the draw reaches several kernels
+
+
 def test_split_k_forced_and_auto(rt, nb):
     # forced: every ring variant, several slice counts, residues along M, both output types
     for variant, (bm, bn) in ((4, (128, 128)), (5, (256, 128)), (6, (256, 256))):
