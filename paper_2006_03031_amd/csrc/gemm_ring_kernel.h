@@ -74,7 +74,12 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   const int KS = (stages_all - stage0) < stages_per ? (stages_all - stage0) : stages_per;
   const u16* __restrict__ A = (const u16*)g.a + (long long)z * g.sa + (stage0 << KSH);
   const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb + (stage0 << KSH);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the thread index goes through an empty volatile statement: a workgroup calls this body once
+  // per tile, and without it the compiler keeps every per-lane address computed from it alive
+  // from one tile to the next, which pushed the 256x256 tile 50-90 registers over its budget)
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
   // loads: pass i covers chunk ids i*NT + tid: row = i*(NT/4) + (tid >> 2), slot = tid & 3.

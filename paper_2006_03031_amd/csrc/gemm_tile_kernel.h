@@ -39,7 +39,8 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, const int m0, 
   const u16* __restrict__ B = (const u16*)g.b + (long long)z * g.sb;
   const int M = g.M, N = g.N, K = g.K;
 
-  const int tid = threadIdx.x;
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));  // recomputed per tile, see gemm_ring_body
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
