@@ -323,6 +323,26 @@ def test_config5_ragged_ffn_sampled_rows(rt, nb):
         assert _err(from_dev(y)[rows], ref_y) <= TOL, ("ffn2", M)
 
 
+def test_config5_fixed_sizes_up_to_the_maximum(rt, nb):
+    """M = 2048, 4096, 8192 and 16384 (32 sequences of 512 tokens, the largest total config 5 can
+    draw: four rounds of tiles per compute unit), one row past each, FFN1 and FFN2 on sampled rows."""
+    to_dev, _, from_dev, _ = _dev()
+    (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
+    w1, b1 = wl.dense_weights(5, 0, N1, K1)
+    w2, b2 = wl.dense_weights(5, 1, N2, K2)
+    dw1, db1, dw2, db2 = to_dev(w1), to_dev(b1), to_dev(w2), to_dev(b2)
+    x = wl.activations(5, 777, 16385, K1)
+    xd = to_dev(x)
+    rng = np.random.default_rng(57)
+    for M in (2048, 4096, 8192, 8193, 16384, 16385):
+        h = rt.dense(xd[:M], dw1, db1, EPI[e1])
+        y = rt.dense(h, dw2, db2, EPI[e2])
+        rows = _sampled_rows(M, 160, 64, rng)
+        hg = from_dev(h)
+        assert _err(hg[rows], oracle.dense(x.f32[rows], w1.f32, b1.f32, e1)) <= TOL, ("ffn1", M)
+        assert _err(from_dev(y)[rows], oracle.dense(hg[rows], w2.f32, b2.f32, e2)) <= TOL, ("ffn2", M)
+
+
 def test_config5_residue_sweep_2048_plus_r(rt, nb):
     to_dev, _, from_dev, _ = _dev()
     (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
