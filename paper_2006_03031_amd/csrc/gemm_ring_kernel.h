@@ -279,13 +279,25 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     for (int i = 0; i < TN; ++i) wb[0][i] = as_bf16x8(b_rd[i * 16 * CH]);
     // reads of the other half of a row: logical chunk + 4, i.e. physical chunk ^ 4
     const int half = ((fr_phys ^ 4) - fr_phys);
-    auto half_step = [&](const uint4* a_nx, const uint4* b_nx, auto cur_tag) {
+    // load u of a stage (0 .. LD-1): the A passes first, then the B passes
+    auto dma_one = [&](int k0, int slot_, int u) {
+      if (u < A_LD)
+        dma16_so(a_off[u], a_base + k0, a_dst + slot_ * (BMP * CH * 16) + u * NT * 16);
+      else
+        dma16_so(b_off, b_base + (u - A_LD) * b_pass + k0, b_dst + slot_ * (BN * CH * 16) + (u - A_LD) * NT * 16);
+    };
+    // ld_k0 >= 0: this half also issues the ring loads of one stage, spread over its weight tiles
+    auto half_step = [&](const uint4* a_nx, const uint4* b_nx, auto cur_tag, int ld_k0, int ld_slot) {
       constexpr int CUR = decltype(cur_tag)::value;
 #pragma unroll
       for (int i = 0; i < TN; ++i) {
         wb[CUR ^ 1][i] = as_bf16x8(b_nx[i * 16 * CH]);
 #pragma unroll
         for (int x = i * TM / TN; x < (i + 1) * TM / TN; ++x) xa[CUR ^ 1][x] = as_bf16x8(a_nx[x * 16 * CH]);
+        if (CUR == 1) {
+#pragma unroll
+          for (int u = i * LD / TN; u < (i + 1) * LD / TN; ++u) dma_one(ld_k0, ld_slot, u);
+        }
         asm volatile("" ::: "memory");
 #pragma unroll
         for (int j = 0; j < TM; ++j) mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
@@ -296,7 +308,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     int slot = 0;
     for (int ks = 0; ks < KS; ++ks) {
       // first half: multiply k 0..31 of stage ks, read its k 32..63
-      half_step(a_rd + slot * (BMP * CH) + half, b_rd + slot * (BN * CH) + half, T0{});
+      half_step(a_rd + slot * (BMP * CH) + half, b_rd + slot * (BN * CH) + half, T0{}, 0, 0);
       // every read of this stage's slot has been issued; once they have returned and every wave
       // is here the slot can be refilled, and stage ks+1 has landed when only the S-2 younger
       // stages are in flight
@@ -304,10 +316,11 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
       __syncthreads();
       const int ld = ks + S;
-      dma(ld < KS ? ld : KS - 1, slot);  // past the end of K: the last stage again, never read
+      const int ld_k0 = (ld < KS ? ld : KS - 1) << KSH;  // past the end of K: the last stage again, never read
+      const int ld_slot = slot;
       slot = slot + 1 == S ? 0 : slot + 1;
-      // second half: multiply k 32..63 of stage ks, read k 0..31 of stage ks+1
-      half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{});
+      // second half: multiply k 32..63 of stage ks, read k 0..31 of stage ks+1, refill the freed slot
+      half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{}, ld_k0, ld_slot);
     }
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
   }
