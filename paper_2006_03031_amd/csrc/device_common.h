@@ -25,25 +25,22 @@ __device__ __forceinline__ u16 f2bf(float f) {
   return (u16)(u >> 16);
 }
 
-// gelu(v) = v/2 (1 + erf(v / sqrt 2)) = v/2 + |v/2| erf(|v| / sqrt 2), with erf(|x|) by the
-// three-term rational-times-Gaussian form of Abramowitz & Stegun 7.1.25 (|error| <= 2.5e-5, far
-// below the bfloat16 spacing of the result) on the hardware reciprocal and exp2: nine ordinary
-// and two quarter-rate instructions per element.  The epilogue of a GELU layer is bound by
-// exactly these instructions (128 outputs per lane with nothing to overlap them), so the
-// five-term form (7.1.26, 1.5e-7) and the library erff cost measurably more for accuracy the
-// output format cannot hold.  Reading the function from a 1024-segment table of chords in LDS
-// (five ordinary instructions and one data-dependent 8-byte read per element) was measured too:
-// 2-6 % slower per kernel, the reads' bank conflicts cost more than the arithmetic they replace.
+// gelu(v) = v/2 (1 + erf(v / sqrt 2)), evaluated as v * sigmoid(a v + b v^3 + c v^5) with the
+// constants of fit_gelu_sigmoid.py (largest deviation from the erf form 2.5e-5, an order of
+// magnitude below the bfloat16 spacing of the result; v^2 is clamped at 81, beyond which the
+// sigmoid is 0 or 1): seven ordinary instructions plus the hardware exp2 and reciprocal.  The
+// epilogue of a GELU layer is bound by exactly these instructions (128 outputs per lane with
+// nothing to overlap them): the three-term rational-times-Gaussian erf of Abramowitz & Stegun
+// 7.1.25 (same accuracy, eleven instructions) was the previous form, 7.1.26 and the library erff
+// cost more still.  Reading the function from a 1024-segment table of chords in LDS (five ordinary
+// instructions and one data-dependent 8-byte read per element) was measured too: 2-6 % slower per
+// kernel, the reads' bank conflicts cost more than the arithmetic they replace.
 __device__ __forceinline__ float gelu_erf(float v) {
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.33267251f, fabsf(v), 1.0f));  // 0.47047 / sqrt 2
-  float p = fmaf(0.7478556f, t, -0.0958798f);
-  p = fmaf(p, t, 0.3480242f);
-  p *= t;
-  const float u = v * 0.84932180f;                  // sqrt(log2(e) / 2)
-  const float e = __builtin_amdgcn_exp2f(-(u * u));  // exp(-v^2 / 2)
-  const float r = fmaf(-p, e, 1.0f);                 // erf(|v| / sqrt 2)
-  const float hv = 0.5f * v;
-  return fmaf(fabsf(hv), r, hv);
+  const float t = fminf(v * v, 81.0f);
+  float p = fmaf(0.0010142630f, t, -0.10677572f);  // -log2(e) (a + b t + c t^2)
+  p = fmaf(p, t, -2.3011212f);
+  const float e = __builtin_amdgcn_exp2f(p * v);    // exp(-(a v + b v^3 + c v^5))
+  return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 __device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
