@@ -50,18 +50,18 @@ static const int64_t kCUs = kComputeUnits;
 static double tile_cost(int variant, int64_t K, int epilogue, int bm = 0) {
   double eff;
   switch (variant) {
-    case NIMBLE_VAR_T32x128: eff = 0.236; break;
-    case NIMBLE_VAR_T64x128: eff = 0.474; break;
-    case NIMBLE_VAR_T128x128: eff = 0.589; break;
-    case NIMBLE_VAR_T256x128: eff = 0.982; break;
+    case NIMBLE_VAR_T32x128: eff = 0.202; break;
+    case NIMBLE_VAR_T64x128: eff = 0.450; break;
+    case NIMBLE_VAR_T128x128: eff = 0.560; break;
+    case NIMBLE_VAR_T256x128: eff = 1.031; break;
     case NIMBLE_VAR_T256x256: eff = 1.10; break;
     default: return 1e30;
   }
   const double k0 = (epilogue == NIMBLE_EPI_BIAS_GELU_ERF) ? 256.0 : 128.0;
   // a tile of another height loads the same weight panel for fewer or more rows: measured
-  // time(bm) / time(256) = 0.13 + 0.87 bm/256 for the 256-wide tile (bm = 128..320)
+  // time(bm) / time(256) = 0.09 + 0.91 bm/256 for the 256-wide tile (bm = 128..320)
   const double height = (bm > 0 && bm != kVariants[variant].bm)
-                            ? 0.1325 + 0.8675 * (double)bm / (double)kVariants[variant].bm : 1.0;
+                            ? 0.0925 + 0.9075 * (double)bm / (double)kVariants[variant].bm : 1.0;
   return (double)kVariants[variant].bm * kVariants[variant].bn * ((double)K + k0) * height / eff;
 }
 
@@ -92,7 +92,7 @@ static const double kUsPerUnit = 4.4e-7;
 static const double kLaunchGapUs = 3.5;
 // The same gap as it shows between a K-split kernel and its reduction, whose launch the
 // hardware queue has already decoded while the first kernel runs.
-static const double kSplitGapUs = 1.65;
+static const double kSplitGapUs = 1.80;
 
 // Weights above this size are taken to come from HBM on every call (the L2s hold 32 MB, the
 // memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
@@ -116,12 +116,12 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
   // a workgroup cannot go faster than its loads arrive through the direct global->LDS path:
   // a 32-wide stage of (bm + bn) rows costs a lone workgroup 0.13 .. 0.3 us.  A GELU epilogue
   // adds about a microsecond to such a latency-bound tile.
-  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.146, 0.161, 0.321, 0.339, 0.30};
+  static const double kStageFloorUs[NIMBLE_VAR_COUNT] = {0, 0, 0.1665, 0.161, 0.382, 0.237, 0.345};
   // time of a tile in a nearly empty last round relative to a full one
-  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.20, 0.43, 0.84, 0.67, 0.73};
+  static const double kLoneTile[NIMBLE_VAR_COUNT] = {0, 0, 0.185, 0.388, 0.678, 0.598, 0.659};
   const int64_t stages = ceil_div(k_slice, 32);
   const bool gelu = sk == 1 && epilogue == NIMBLE_EPI_BIAS_GELU_ERF;
-  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 0.94 : 0.0);
+  const double latency_floor = (double)stages * kStageFloorUs[v] + (gelu ? 0.05 : 0.0);
   const double t_full = tile_cost(v, k_slice, sk > 1 ? NIMBLE_EPI_NONE : epilogue, bm) * kUsPerUnit;
   // a round is one tile per compute unit for the 8-wave tiles, two for the smaller ones
   const int64_t slots = kCUs * kTilesPerCU[v];
@@ -175,7 +175,7 @@ static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
   const double mt = (double)ceil_div(rows, 16 * nblocks);
   const double blocks = (double)ceil_div(rows, 64);
   const double bytes = (double)N * (double)K * 2.0;
-  const double rate = bytes > kCachedWeightBytes ? 5.94e6 : 7.15e6;  // bytes per microsecond
+  const double rate = bytes > kCachedWeightBytes ? 5.94e6 : 6.79e6;  // bytes per microsecond
   const double stream = bytes / rate * (1.0 + 0.553 * (double)rows / (double)nblocks / 16.0);
   const double walk = (double)ceil_div(K, 128) * mt * 0.126;
   return kLaunchUs + blocks * (stream > walk ? stream : walk);
