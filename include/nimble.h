@@ -194,7 +194,10 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
 /* batch_matmul with dynamic M (and N or K when they are the same symbol):
  *   trans_b != 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,n,k]
  *   trans_b == 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,k,n]
- * a, b bf16; c of out_dtype; f32 accumulation. */
+ * a, b bf16; c of out_dtype; f32 accumulation.  With trans_b == 0 the tiled kernels run on b
+ * transposed into the workspace (nimble_batch_matmul_plan gives its size, batch*N*K*2 bytes,
+ * when K is a multiple of 8 and a tile suits the shape); with less workspace than that, or none,
+ * a bounds-checked kernel reads b as it is. */
 int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch, int64_t M,
                             int64_t N, int64_t K, int trans_b, float alpha, int out_dtype,
                             void* workspace, size_t workspace_bytes, void* stream);

@@ -45,6 +45,29 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// b [T, K, N] -> bt [T, N, K] (bf16), 32 x 32 tiles through LDS: the NN batch_matmul is run as
+// the NT one on the transposed operand, which lives in the caller's workspace.
+__global__ void __launch_bounds__(256)
+    transpose_kn_kernel(const u16* __restrict__ b, u16* __restrict__ bt, int K, int N) {
+  __shared__ u16 tile[32][33];
+  const long long plane = (long long)K * N;
+  const u16* src = b + blockIdx.z * plane;
+  u16* dst = bt + blockIdx.z * plane;
+  const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int k = k0 + ty + 8 * r, n = n0 + tx;
+    if (k < K && n < N) tile[ty + 8 * r][tx] = src[(long long)k * N + n];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int n = n0 + ty + 8 * r, k = k0 + tx;
+    if (n < N && k < K) dst[(long long)n * K + k] = tile[tx][ty + 8 * r];
+  }
+}
+
 __global__ void __launch_bounds__(256)
     softmax_rows_kernel(const float* __restrict__ s, u16* __restrict__ p, long long rows, int cols) {
   const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);

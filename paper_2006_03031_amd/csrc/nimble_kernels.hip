@@ -229,10 +229,11 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
                             int64_t N, int64_t K, int trans_b, float alpha, int out_dtype,
                             void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
-  (void)workspace;
   if (batch < 0 || M < 0 || N < 0 || K < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32)
     return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  if (workspace_bytes > 0 && !workspace) return fail(NIMBLE_ERR_NULL, "workspace_bytes > 0 with a null workspace");
+  if (workspace && misaligned(workspace)) return fail(NIMBLE_ERR_ALIGN, "workspace must be 16-byte aligned");
   nimble_plan p;
   int rc = nimble_batch_matmul_plan(batch, M, N, K, trans_b, out_dtype, &p);
   if (rc != NIMBLE_OK) return rc;
@@ -240,9 +241,17 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
   if (!a || !b || !c) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
   if (misaligned(a) || misaligned(b) || misaligned(c))
     return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
-  if (workspace_bytes < p.workspace_bytes)
-    return fail(NIMBLE_ERR_WORKSPACE, "workspace of %zu bytes, plan needs %llu", workspace_bytes,
-                (unsigned long long)p.workspace_bytes);
+  // the NN product on the tiled kernels needs b transposed into the workspace: without enough of
+  // it the bounds-checked kernel does the job (the plan is made within the scratch the caller brought)
+  bool transpose_b = false;
+  if (!trans_b && p.variant >= NIMBLE_VAR_T32x128) {
+    if (workspace_bytes >= p.workspace_bytes && batch <= 65535) {
+      transpose_b = true;
+    } else {
+      rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), &p);
+      if (rc != NIMBLE_OK) return rc;
+    }
+  }
   GemmArgs g{};
   g.a = a;
   g.b = b;
@@ -261,6 +270,16 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
   g.out_f32 = out_dtype == NIMBLE_F32;
   g.b_is_kn = trans_b ? 0 : 1;
   g.batch = (int)batch;
+  if (transpose_b) {
+    dim3 tgrid((unsigned)((N + 31) / 32), (unsigned)((K + 31) / 32), (unsigned)batch);
+    hipLaunchKernelGGL(transpose_kn_kernel, tgrid, dim3(256), 0, (hipStream_t)stream, (const u16*)b, (u16*)workspace,
+                       (int)K, (int)N);
+    rc = check_hip(hipGetLastError(), "transpose launch");
+    if (rc != NIMBLE_OK) return rc;
+    g.b = workspace;
+    g.ldb = (int)K;
+    g.b_is_kn = 0;
+  }
   // batch slices of a K-contiguous operand stay 16-byte aligned only if M*K (N*K) is a multiple of 8
   if (p.variant != NIMBLE_VAR_GENERIC && (((M * K) & 7) != 0 || ((N * K) & 7) != 0)) {
     rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), &p);

@@ -100,12 +100,14 @@ def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilog
 
 
 def batch_matmul(a: torch.Tensor, b: torch.Tensor, trans_b: bool, alpha: float = 1.0,
-                 out_dtype: int = nb.BF16, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 out_dtype: int = nb.BF16, out: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     T, M, N = nb.batch_matmul_shape(tuple(a.shape), tuple(b.shape), trans_b)
     K = a.shape[2]
     c = out if out is not None else _alloc((T, M, N), out_dtype, a.device)
+    ws = workspace if workspace is not None else default_workspace(a.device)   # b transposed, for the NN product
     nb.nimble_batch_matmul_dyn(a.data_ptr(), b.data_ptr(), c.data_ptr(), T, M, N, K, trans_b, alpha,
-                               out_dtype, 0, 0, _stream())
+                               out_dtype, ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
     return c
 
 

@@ -600,6 +600,31 @@ def test_batch_matmul_general_shapes(rt, nb):
             assert _err(from_dev(c), ref) <= TOL, (T, M, N, K, trans_b, od)
 
 
+def test_batch_matmul_nn_on_the_tiled_kernels_and_without_workspace(rt, nb):
+    """b [T,K,N] with K a multiple of 8: the plan is the NT launch on b transposed into the workspace
+    (config 4's P.V at L = 128..512 among the shapes); a caller that brings no workspace gets the
+    bounds-checked kernel and the same result to within rounding."""
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(10)
+    none = torch.empty(0, dtype=torch.uint8, device="cuda")
+    for (T, M, N, K) in [(12, 256, 64, 256), (12, 512, 64, 512), (8, 400, 64, 400), (7, 301, 136, 168), (2, 2050, 8, 1024)]:
+        p = nb.batch_matmul_plan(T, M, N, K, False)
+        assert p.name != "generic" and p.workspace_bytes == T * N * K * 2, (T, M, N, K, p.name)
+        a, b = wl.uniform_bf16(rng, (T, M, K)), wl.uniform_bf16(rng, (T, K, N))
+        ref = oracle.batch_matmul(a.f32, b.f32, False, 0.5)
+        for od in (nb.BF16, nb.F32):
+            tiled = rt.batch_matmul(to_dev(a), to_dev(b), False, 0.5, od)
+            plain = rt.batch_matmul(to_dev(a), to_dev(b), False, 0.5, od, workspace=none)
+            assert _err(from_dev(tiled), ref) <= TOL, ("tiled", T, M, N, K, od)
+            assert _err(from_dev(plain), ref) <= TOL, ("plain", T, M, N, K, od)
+    # K not a multiple of 8: no tiled plan, no workspace asked for
+    p = nb.batch_matmul_plan(4, 33, 64, 33, False)
+    assert p.name == "generic" and p.workspace_bytes == 0
+    # small products stay on the bounds-checked kernel: the extra launch would cost more than it saves
+    p = nb.batch_matmul_plan(12, 128, 64, 128, False)
+    assert p.name == "generic" and p.workspace_bytes == 0
+
+
 def test_softmax_rows_on_gpu(rt, nb):
     _, f32_to_dev, from_dev, _ = _dev()
     rng = np.random.default_rng(10)
