@@ -295,3 +295,50 @@ def test_storage_arena_offsets_alignment_and_overflow():
     assert arena.offset == 0 and used > 0
     c = arena.alloc((3, 5), nb.BF16)
     assert c.data_ptr() == a.data_ptr()    # the block is reused from the start
+
+
+def test_plan_invariants_on_random_shapes():
+    # whatever the cost model picks, the plan must describe a launch that covers the problem exactly
+    rng = np.random.default_rng(7)
+    names = set()
+    for _ in range(600):
+        M = int(rng.choice([rng.integers(1, 70), rng.integers(1, 3000), rng.integers(1, 20000)]))
+        N = int(rng.choice([rng.integers(1, 600), rng.integers(1, 40) * 128, rng.integers(1, 17) * 256]))
+        K = int(rng.choice([rng.integers(1, 600), rng.integers(1, 130) * 32, rng.integers(1, 65) * 64]))
+        epi = int(rng.integers(0, 3))
+        p = nb.dense_plan(M, N, K, epi)
+        names.add(p.name)
+        assert p.k * p.bm + p.r == M and 0 <= p.r < p.bm
+        if p.name == "generic":
+            assert K % 8 != 0
+            continue
+        assert K % 8 == 0
+        if p.name == "skinny16":
+            blocks = p.grid[1]
+            assert p.grid[0] == -(-N // 16) and -(-M // (16 * blocks)) <= 4 and p.workspace_bytes == 0
+            continue
+        rows = p.split_rows if p.split_rows else M
+        assert p.grid[0] == -(-rows // p.bm) * -(-N // p.bn)
+        if p.split_rows:
+            assert p.split_rows % p.bm == 0 and 0 < p.split_rows < M and p.split_k == 1
+        if p.split_k > 1:
+            assert N % p.bn == 0 and K % 32 == 0 and p.workspace_bytes == p.split_k * M * N * 4
+            assert p.workspace_bytes <= 64 << 20   # plans are made within the default scratch
+            stages = K // 32
+            per = -(-stages // p.split_k)
+            assert per * (p.split_k - 1) < stages          # every slice has work
+        else:
+            assert p.workspace_bytes == 0
+        if p.bm not in (32, 64, 128, 256):                 # a reduced or raised height of the 256-wide tile
+            assert p.name == "t256x256" and N % 256 == 0 and K % 32 == 0
+    assert {"skinny16", "t32x128", "t256x256"} <= names
+
+
+def test_batch_matmul_plan_nn_workspace():
+    # NN on the tiled kernels needs b transposed: the plan asks for exactly that much scratch
+    p = nb.batch_matmul_plan(12, 512, 64, 512, False)
+    assert p.name != "generic" and p.workspace_bytes == 12 * 64 * 512 * 2 and p.grid[2] == 12
+    for (T, M, N, K) in [(12, 128, 64, 128), (4, 33, 64, 33), (2, 129, 40, 257), (1, 5000, 64, 12)]:
+        p = nb.batch_matmul_plan(T, M, N, K, False)
+        assert p.name == "generic" and p.workspace_bytes == 0
+    assert nb.batch_matmul_plan(12, 512, 512, 64, True).workspace_bytes == 0
