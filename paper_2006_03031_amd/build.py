@@ -33,6 +33,96 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def device_assembly() -> str:
+    """The gfx950 assembly of the kernels, as text (same flags as the library)."""
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "kernels.s")
+        cmd = [
+            "hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "--cuda-device-only", "-S",
+            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            os.path.join(CSRC, "nimble_kernels.hip"), "-o", out,
+        ]
+        proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc -S failed:\n" + proc.stdout[-4000:])
+        with open(out) as f:
+            return f.read()
+
+
+def _agprs(text: str) -> set:
+    import re
+    regs = set()
+    for lo, hi in re.findall(r"\ba\[(\d+):(\d+)\]", text):
+        regs.update(range(int(lo), int(hi) + 1))
+    regs.update(int(r) for r in re.findall(r"\ba(\d+)\b", text))
+    return regs
+
+
+def asm_mfma_findings(asm: str, wait_states: int = 18):
+    """Checks of the compiler's output around the MFMAs that the kernels write as volatile
+    statements.  The compiler does not know that those are matrix instructions and adds no wait
+    states behind them, so anything else that touches their result registers too soon reads (or
+    overwrites) them before the matrix core has written them.  Returns (hazards, spills):
+      hazards: (kernel, line number, instruction) of every instruction outside such statements
+               that names an accumulation register written by such an MFMA fewer than
+               `wait_states` issue slots earlier (an MFMA counts 8 slots, s_nop N counts N+1);
+      spills:  (kernel, block label, count) of scratch accesses in basic blocks that hold such MFMAs
+               (register spills inside a main loop)."""
+    import re
+    hazards, spills = [], []
+    kernel, block, in_stmt = None, None, False
+    block_mfma, block_scratch = 0, 0
+    recent = []  # [age in issue slots, registers written] per statement-MFMA still within reach
+
+    def close_block():
+        if block_mfma and block_scratch:
+            spills.append((kernel, block, block_scratch))
+
+    for no, line in enumerate(asm.split("\n"), 1):
+        t = line.strip()
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            close_block()
+            kernel, block, block_mfma, block_scratch, recent = m.group(1), "entry", 0, 0, []
+            continue
+        m = re.match(r"^(\.LBB\w+):", line)
+        if m:
+            close_block()
+            block, block_mfma, block_scratch = m.group(1), 0, 0
+            continue
+        if t.startswith(";;#ASMSTART"):
+            in_stmt = True
+            continue
+        if t.startswith(";;#ASMEND"):
+            in_stmt = False
+            continue
+        if not t or t[0] in ";." or t.endswith(":"):
+            continue
+        if t.startswith("v_mfma"):
+            recent = [[age + 8, regs] for age, regs in recent]
+            if in_stmt:
+                block_mfma += 1
+                recent.append([0, _agprs(t.split(None, 1)[1].split(",")[0])])
+            continue
+        if t.startswith("s_nop"):
+            n = int(t.split()[1], 0) + 1
+            recent = [[age + n, regs] for age, regs in recent]
+            continue
+        if t.startswith("scratch_"):
+            block_scratch += 1
+        touched = _agprs(t)
+        if touched:
+            for age, regs in recent:
+                if age < wait_states and touched & regs:
+                    hazards.append((kernel, no, t))
+                    break
+        recent = [[age + 1, regs] for age, regs in recent if age + 1 < 4 * wait_states]
+    close_block()
+    return hazards, spills
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True

@@ -76,11 +76,35 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
 __device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// The compiler does not know that the statement above is a matrix instruction, so it adds none of
+// the wait states a matrix result needs before anything else reads its registers (a copy, a
+// spill store, the epilogue's arithmetic), and it may place such a reader directly behind the
+// statement.  The last MFMA of a tile's last stage therefore carries the wait states itself, in
+// the same statement so that nothing can come in between: `last` (wave-uniform) != 0 runs 32 idle
+// cycles, by the end of which this result and those of all earlier MFMAs have been written.
+__device__ __forceinline__ void mfma_acc_last(f32x4& acc, const bf16x8& a, const bf16x8& b, int last) {
+  asm volatile(
+      "v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\t"
+      "s_cmp_eq_u32 %3, 0\n\t"
+      "s_cbranch_scc1 .Lnimble_mfma_done_%=\n\t"
+      "s_nop 15\n\t"
+      "s_nop 15\n"
+      ".Lnimble_mfma_done_%=:"
+      : "+a"(acc)
+      : "v"(a), "v"(b), "s"(__builtin_amdgcn_readfirstlane(last))
+      : "scc");
+}
 
 // Same, addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit per-lane
 // byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
 __device__ __forceinline__ void dma16_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase),
+               "s"(lds_addr)
+               : "memory", "m0");
+}
+// One dword per lane: a wave instruction fills 256 contiguous bytes of LDS.
+__device__ __forceinline__ void dma4_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1\n" ::"v"(voff), "s"(sbase),
                "s"(lds_addr)
                : "memory", "m0");
 }

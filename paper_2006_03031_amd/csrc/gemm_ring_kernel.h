@@ -126,18 +126,20 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
 #pragma unroll
     for (int j = 0; j < TM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // The tile's BN bias values are fetched now, ahead of every other load, and parked in LDS behind
-  // the ring, so that the epilogue does not begin with a round trip to memory.  Issued as a
-  // volatile statement before the first ring load: the wait for stage 0 below then covers it
-  // (loads complete in order), and the compiler's own wait counting never sees it.  The 288- and
-  // 320-row tiles leave no LDS for it and load the bias in the epilogue.
+  // The tile's BN bias values are fetched now, ahead of every other load, into LDS behind the ring,
+  // so that the epilogue does not begin with a round trip to memory: the first BN/128 waves each
+  // bring 256 bytes with one direct global->LDS load.  Loads complete in order, so the wait for
+  // stage 0 below covers it, and the barrier after that wait publishes it.  (No register is
+  // involved: a load into a register that the compiler cannot see complete may be spilled or
+  // copied before its data has arrived.)  The 288- and 320-row tiles leave no LDS for it and load
+  // the bias in the epilogue.
   constexpr bool BIAS_LDS = S * (BMP + BN) * CH * 16 + BN * 2 <= 160 * 1024;
   u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * CH);
   const bool park_bias = BIAS_LDS && g.epilogue != NIMBLE_EPI_NONE && !g.out_f32;
-  uint2 bias_pre;
-  if (park_bias) {  // uniform branch; every lane loads (lanes past BN/4 repeat an earlier lane's 8 bytes)
-    const u16* src = (const u16*)g.bias + n0 + (tid & (BN / 4 - 1)) * 4;
-    asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(bias_pre) : "v"(src) : "memory");
+  if (park_bias && wave < BN / 128) {  // whole waves
+    const int wu = __builtin_amdgcn_readfirstlane(wave);
+    dma4_so((uint32_t)lane * 4u, (const u16*)g.bias + n0 + wu * 128,
+            __builtin_amdgcn_readfirstlane(lds_addr_of(bias_lds)) + wu * 256);
   }
 
   if constexpr (WIDE) {
@@ -158,7 +160,6 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   __syncthreads();
-  if (park_bias && tid < BN / 4) *(uint2*)(bias_lds + tid * 4) = bias_pre;  // read after the epilogue's barrier
 
   if constexpr (MODE == RING_PINGPONG) {
     // Waves w and w + NW/2 share a SIMD.  The workgroup runs in two groups half a step out of
@@ -251,7 +252,12 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
           xa[CUR ^ 1][x] = as_bf16x8(a_nx[x * 64]);
         asm volatile("" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < TM; ++j) mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+        for (int j = 0; j < TM; ++j) {
+          if (i == TN - 1 && j == TM - 1)
+            mfma_acc_last(acc[i][j], wb[CUR][i], xa[CUR][j], ks + 1 >= KS);
+          else
+            mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+        }
       }
     };
     using T0 = std::integral_constant<int, 0>;
@@ -262,10 +268,8 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       stage(ks + 1, T1{});
     }
     if (ks < KS) stage(ks, T0{});  // odd number of stages
-    // loads past the end of K may still be in flight into the ring the epilogue is about to reuse;
-    // the MFMAs above are opaque to the compiler's hazard handling: let the last results land
-    // before anything reads the accumulators
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // loads past the end of K may still be in flight into the ring the epilogue is about to reuse
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   } else if constexpr (MODE == RING_WIDE) {
     // Same straight-line schedule as above on stages of 64 k: two halves of 32 k per stage, the
     // fragments of the next half read into the other register set in between the MFMAs of the
@@ -286,21 +290,27 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       else
         dma16_so(b_off, b_base + (u - A_LD) * b_pass + k0, b_dst + slot_ * (BN * CH * 16) + (u - A_LD) * NT * 16);
     };
-    // ld_k0 >= 0: this half also issues the ring loads of one stage, spread over its weight tiles
-    auto half_step = [&](const uint4* a_nx, const uint4* b_nx, auto cur_tag, int ld_k0, int ld_slot) {
+    // second halves (CUR == 1) also issue the ring loads of one stage, spread over their weight
+    // tiles (ld_k0 < 0 in a two-slot ring: past the end of K, nothing to load)
+    auto half_step = [&](const uint4* a_nx, const uint4* b_nx, auto cur_tag, int ld_k0, int ld_slot, int last) {
       constexpr int CUR = decltype(cur_tag)::value;
 #pragma unroll
       for (int i = 0; i < TN; ++i) {
         wb[CUR ^ 1][i] = as_bf16x8(b_nx[i * 16 * CH]);
 #pragma unroll
         for (int x = i * TM / TN; x < (i + 1) * TM / TN; ++x) xa[CUR ^ 1][x] = as_bf16x8(a_nx[x * 16 * CH]);
-        if (CUR == 1) {
+        if (CUR == 1 && (S != 2 || ld_k0 >= 0)) {  // uniform
 #pragma unroll
           for (int u = i * LD / TN; u < (i + 1) * LD / TN; ++u) dma_one(ld_k0, ld_slot, u);
         }
         asm volatile("" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < TM; ++j) mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+        for (int j = 0; j < TM; ++j) {
+          if (CUR == 1 && i == TN - 1 && j == TM - 1)
+            mfma_acc_last(acc[i][j], wb[CUR][i], xa[CUR][j], last);
+          else
+            mfma_acc(acc[i][j], wb[CUR][i], xa[CUR][j]);
+        }
       }
     };
     using T0 = std::integral_constant<int, 0>;
@@ -308,21 +318,28 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     int slot = 0;
     for (int ks = 0; ks < KS; ++ks) {
       // first half: multiply k 0..31 of stage ks, read its k 32..63
-      half_step(a_rd + slot * (BMP * CH) + half, b_rd + slot * (BN * CH) + half, T0{}, 0, 0);
+      half_step(a_rd + slot * (BMP * CH) + half, b_rd + slot * (BN * CH) + half, T0{}, 0, 0, 0);
       // every read of this stage's slot has been issued; once they have returned and every wave
       // is here the slot can be refilled, and stage ks+1 has landed when only the S-2 younger
       // stages are in flight
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
       __syncthreads();
+      // Past the end of K.  S = 2: nothing is loaded (the wait above is for zero loads in flight
+      // whether or not a younger stage was issued), which spares the L2->LDS path two stages' worth
+      // of traffic per tile.  S = 3: the last stage again, into a slot nobody reads any more, so
+      // that the count of loads in flight, and with it the wait count, is the same at every stage;
+      // choosing the wait count per stage instead puts a branch into the stage and ran 3-4 % slower.
+      // (A second copy of the stage code without loads for the last two stages, instead of the
+      // test on ld_k0, cost the 256x256 tile 20 spilled registers and 6 % at ragged M.)
       const int ld = ks + S;
-      const int ld_k0 = (ld < KS ? ld : KS - 1) << KSH;  // past the end of K: the last stage again, never read
+      const int ld_k0 = ld < KS ? (ld << KSH) : (S == 2 ? -1 : ((KS - 1) << KSH));
       const int ld_slot = slot;
       slot = slot + 1 == S ? 0 : slot + 1;
       // second half: multiply k 32..63 of stage ks, read k 0..31 of stage ks+1, refill the freed slot
-      half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{}, ld_k0, ld_slot);
+      half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{}, ld_k0, ld_slot, ks + 1 >= KS);
     }
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (S = 3: the loads past the end of K)
   }
 
   // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
