@@ -95,8 +95,8 @@ __device__ __forceinline__ void mfma_acc_last(f32x4& acc, const bf16x8& a, const
       : "scc");
 }
 
-// Same, addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit per-lane
-// byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
+// The direct global -> LDS load addressed as a wave-uniform 64-bit base (in SGPRs) plus a 32-bit
+// per-lane byte offset, which keeps per-lane 64-bit pointers out of the vector registers.
 __device__ __forceinline__ void dma16_so(uint32_t voff, const void* sbase, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n" ::"v"(voff), "s"(sbase),
                "s"(lds_addr)
