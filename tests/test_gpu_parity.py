@@ -127,12 +127,14 @@ def test_auto_dispatch_picks_a_tile_height_that_fills_the_rounds(rt, nb):
         assert _err(from_dev(y)[rows], ref) <= TOL, (M, N, K)
 
 
-@pytest.mark.parametrize("variant", [4, 5, 6])
+@pytest.mark.parametrize("variant", sorted(TILED))
 def test_ring_variants_short_and_odd_stage_counts(rt, nb, variant):
-    # K of 1, 2, 3, 5 and 9 ring stages: the pipeline prologue, the tail waits and the
-    # ping-pong barrier count must hold when there are fewer stages than ring slots
+    # K of 1, 2, 3, 5 and 9 stages of 32 (the 32-wide ring) and of 1 to 4 stages of 64 (the 64-wide
+    # ring with two or three slots): the pipeline prologue, the tail waits, the loads that are or
+    # are not issued past the end of K and the ping-pong barrier count must hold when there are
+    # fewer stages than ring slots
     bm, bn = TILED[variant]
-    for K in (32, 64, 96, 160, 288):
+    for K in (32, 64, 96, 128, 160, 192, 256, 288):
         _sweep(rt, nb, variant, N=bn, K=K, Ms=[bm, bm + 5, 2 * bm], epilogue="bias")
 
 
