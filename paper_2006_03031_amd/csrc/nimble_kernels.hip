@@ -93,7 +93,14 @@ static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t 
   // 16-row tiles per workgroup: the rows spread evenly over the plan's row blocks (at most 4 each)
   const int mt = (s.M + 16 * (int)p.grid[1] - 1) / (16 * (int)p.grid[1]);
   switch (mt) {
-    case 1: hipLaunchKernelGGL((skinny_kernel<1, LSTM>), grid, block, 0, st, s); break;
+    case 1:
+      // a grid that leaves compute units with one workgroup at most, and more than one batch of
+      // eight steps per wave: twice the loads per batch
+      if (!LSTM && (uint64_t)p.grid[0] * p.grid[1] <= (uint64_t)kComputeUnits && s.K > 1024)
+        hipLaunchKernelGGL((skinny_kernel<1, false, 16>), grid, block, 0, st, s);
+      else
+        hipLaunchKernelGGL((skinny_kernel<1, LSTM>), grid, block, 0, st, s);
+      break;
     case 2: hipLaunchKernelGGL((skinny_kernel<2, LSTM>), grid, block, 0, st, s); break;
     case 3: hipLaunchKernelGGL((skinny_kernel<3, LSTM>), grid, block, 0, st, s); break;
     default: hipLaunchKernelGGL((skinny_kernel<4, LSTM>), grid, block, 0, st, s); break;
