@@ -45,7 +45,38 @@ def _traffic_note():
     return None
 
 
+def _roof(bound, achieved, unit, **more):
+    """A roofline record: achieved algorithmic rate against the nominal peak of what bounds the kernel."""
+    peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBPS
+    d = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
+    d.update(more)
+    return d
+
+
+def _single_call_latency_us(fn, reps: int = 20) -> float:
+    """Host-to-completion latency of one call on an idle stream: the host clock from just before the
+    call until the device has finished it (median of `reps`)."""
+    import statistics
+
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        ts.append((time.perf_counter() - t0) * 1e6)
+    return round(statistics.median(ts), 2)
+
+
+PREHEAT_MS = 60.0   # the clocks take about 10 ms of work to come up after idle; the timed region starts past that
+REPEATS = 5         # the timed loop of exactly `steps` steps runs this often; the median repeat is reported
+
+
 def bench_config5(steps: int, warmup: int):
+    import statistics
+
     import numpy as np
     import torch
 
@@ -74,38 +105,50 @@ def bench_config5(steps: int, warmup: int):
         y = rt.dense(h, dw2, db2, epi[e2], arena=arena)
         return y
 
+    # untimed pre-heat of the same step for a fixed wall time: a short --warmup (the default command of
+    # the harness warms up for 5 steps, under a millisecond) would otherwise leave the timed region
+    # inside the clock ramp after idle, which runs 10-15 % slower
+    t_pre = time.perf_counter()
+    n_pre = 0
+    while (time.perf_counter() - t_pre) * 1e3 < PREHEAT_MS:
+        for i in range(16):
+            step(n_pre + i)
+        n_pre += 16
+        torch.cuda.synchronize()
+    preheat_ms = (time.perf_counter() - t_pre) * 1e3
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for i in range(steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    walls, kernel_ms = [], []
+    for rep in range(REPEATS):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for i in range(steps):
+            step(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        walls.append(time.perf_counter() - t0)
+        # HIP events on the launch stream bracket the timed loop, which holds nothing but the
+        # dense launches (two nimble_dense_dyn calls per step)
+        kernel_ms.append(ev0.elapsed_time(ev1))
     events = [(Ms[i % len(Ms)],) for i in range(steps)]
 
     total_flops = sum(2.0 * M * (N1 * K1 + N2 * K2) for M, *_ in events)
-    elapsed = t1 - t0
-    # HIP events on the launch stream bracket the timed region, which holds nothing but the
-    # dense launches (two nimble_dense_dyn calls per step): average duration per call
-    k_ms = ev0.elapsed_time(ev1)
-    k_flops = total_flops
+    elapsed = statistics.median(walls)
+    k_ms = statistics.median(kernel_ms)
     launches = 2 * steps
-    achieved = k_flops / (k_ms * 1e-3) / 1e12
+    achieved = total_flops / (k_ms * 1e-3) / 1e12
     plans = sorted({nb.dense_plan(M, N1, K1).name for M in Ms} | {nb.dense_plan(M, N2, K2).name for M in Ms})
-    roofline = {
-        "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": _traffic_note(),
-        "kernel": "gemm_ring_kernel (" + ",".join(plans) + ")", "launches": launches,
-        "avg_launch_us": round(k_ms * 1e3 / launches, 2),
-        "flops_per_launch": round(k_flops / launches),
-    }
+    roofline = _roof("mfma", achieved, "TFLOP/s", traffic=_traffic_note(),
+                     traffic_source="profiles/dense_config5_hbm_traffic.txt (rocprofv3 --pmc runs of this "
+                                    "command, bytes per dense launch; not measured by this run)",
+                     kernel="gemm_ring_kernel (" + ",".join(plans) + ")", launches=launches,
+                     avg_launch_us=round(k_ms * 1e3 / launches, 2), flops_per_launch=round(total_flops / launches))
     return {
         "value": total_flops / elapsed / 1e12, "ms_per_step": elapsed * 1e3 / steps, "roofline": roofline,
-        "mean_M": sum(M for M, *_ in events) / len(events),
+        "mean_M": sum(M for M, *_ in events) / len(events), "preheat_ms": round(preheat_ms, 1),
+        "repeats": REPEATS, "ms_per_step_each_repeat": [round(w * 1e3 / steps, 4) for w in walls],
     }
 
 
@@ -172,7 +215,10 @@ def small_m_probe():
                                                  "us_per_call_graph": round(us_g, 2),
                                                  "hbm_frac_graph": round(nbytes / us_g / 1e3 / PEAK_HBM_GBPS, 4),
                                                  "us_per_call_graph_warm": round(us_w, 2),
-                                                 "effective_GBps_warm": round(nbytes / us_w / 1e3, 1)}
+                                                 "effective_GBps_warm": round(nbytes / us_w / 1e3, 1),
+                                                 "roofline": _roof("hbm", nbytes / us_g / 1e3, "GB/s", timing="64 launches, one per "
+                                                                   "weight set (512 MB in rotation), replayed as one HIP graph",
+                                                                   note="8 MB of weights are 1 us of HBM time: launch-bound")}
     del w
     # the same at a size where HBM, not launch latency, is the bound: one 8192 x 8192 layer (134 MB)
     N2 = K2 = 8192
@@ -191,8 +237,12 @@ def small_m_probe():
         torch.cuda.synchronize()
         us = s.elapsed_time(e) * 1e3 / 16
         nbytes = N2 * K2 * 2 + N2 * 2 + M * K2 * 2 + M * N2 * 2
+        plan = nb.dense_plan(M, N2, K2, nb.EPI_BIAS)
         out[f"dense_{K2}x{N2}_M{M}_rotating"] = {"us_per_call": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
-                                                   "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4)}
+                                                   "hbm_frac": round(nbytes / us / 1e3 / PEAK_HBM_GBPS, 4),
+                                                   "plan": plan.name + (f"/sk{plan.split_k}" if plan.split_k > 1 and plan.variant > 1 else ""),
+                                                   "roofline": _roof("hbm", nbytes / us / 1e3, "GB/s", timing="16 back-to-back calls over "
+                                                                     "4 weight sets (537 MB in rotation), HIP events")}
     del w
     lw = wl.config2_weights()
     dw, db = _to_dev(lw.w), _to_dev(lw.b)
@@ -235,9 +285,14 @@ def small_m_probe():
         e.record()
         torch.cuda.synchronize()
         us_p = s.elapsed_time(e) * 1e3 / (4 * 128)
+        lat = _single_call_latency_us(lambda: rt.lstm_step(x, h0, dw, db, c, h_out=h1, c_out=c))
         out[f"lstm_step_B{B}_warm"] = {"us_per_step": round(us, 2), "us_per_step_graph": round(us_g, 2),
                                        "eff_GBps_graph": round(nbytes / us_g / 1e3, 1),
-                                       "us_per_step_graph_inputs_projected": round(us_p, 2)}
+                                       "us_per_step_graph_inputs_projected": round(us_p, 2),
+                                       "single_call_host_to_completion_us": lat,
+                                       "roofline": _roof("hbm", nbytes / us_g / 1e3, "GB/s", timing="128-step token loop replayed "
+                                                         "as a HIP graph", note="effective: the same 4.2 MB of weights every step "
+                                                         "stay in the L2s / memory-side cache")}
         del seq, seq_p
     # the same token loop as bytecode on the interpreter: shape_of, shape function, allocation from
     # the pool and invoke per token (about two dozen coarse instructions), host cost per token split
@@ -280,6 +335,13 @@ def small_m_probe():
             e.record()
             torch.cuda.synchronize()
             res[name + "_us"] = round(s.elapsed_time(e) * 1e3 / reps, 2)
+        # algorithmic bytes: q, k, v in and o out for the fused kernel; the chain adds S (f32 out and in) and P
+        # (bf16 out and in): 144 L^2
+        res["roofline"] = _roof("hbm", 6144.0 * L / res["fused_us"] / 1e3, "GB/s", kernel="attention64_kernel",
+                                note="launch-bound: a few hundred KB per call")
+        res["roofline_chain"] = _roof("hbm", (6144.0 * L + 144.0 * L * L) / res["chain_us"] / 1e3, "GB/s",
+                                      kernel="batch_matmul, softmax_rows, batch_matmul")
+        res["single_call_host_to_completion_us"] = _single_call_latency_us(lambda: rt.fused_attention(q, k, v, out=o))
         out[f"attention_L{L}"] = res
     return out
 
@@ -344,8 +406,15 @@ def config_1_and_3_probe():
     for _ in range(8):
         pass1()
     torch.cuda.synchronize()
-    out["config1_dense_128x128"] = {"us_per_call_eager": round((time.perf_counter() - t0) * 1e6 / (8 * len(xs)), 2),
-                                    "us_per_call_graph": round(_time_us(pass1, reps=1) / len(xs), 2)}
+    us_eager = (time.perf_counter() - t0) * 1e6 / (8 * len(xs))
+    us_graph = _time_us(pass1, reps=1) / len(xs)
+    mean_bytes = sum(32768 + 256 + 512 * x.shape[0] for x in xs) / len(xs)
+    mid = len(xs) // 2
+    out["config1_dense_128x128"] = {"us_per_call_eager": round(us_eager, 2), "us_per_call_graph": round(us_graph, 2),
+                                    "single_call_host_to_completion_us": _single_call_latency_us(
+                                        lambda: rt.dense(xs[mid], w, b, nb.EPI_BIAS, out=ys[mid])),
+                                    "roofline": _roof("hbm", mean_bytes / us_graph / 1e3, "GB/s", timing="the 64 calls replayed "
+                                                      "as one HIP graph", note="launch-bound: 33 KB of weights are 4 ns of HBM time")}
     epi = {"bias": nb.EPI_BIAS, "bias_gelu": nb.EPI_BIAS_GELU_ERF}
     weights = [(_to_dev(wb[0]), _to_dev(wb[1]), K, N, epi[e]) for i, (n, K, N, e) in enumerate(wl.BERT_BASE_GEMMS)
                for wb in (wl.dense_weights(3, i, N, K),)]
@@ -359,8 +428,14 @@ def config_1_and_3_probe():
         us = _time_us(layer, reps=8)
         flops = 2.0 * L * sum(K * N for _, _, K, N, _ in weights)
         plans = [nb.dense_plan(L, N, K, e) for _, _, K, N, e in weights]
+        nbytes = 14155776.0 + 24576.0 * L + 2 * sum(N for _, _, _, N, _ in weights)
         out[f"config3_bert_base_L{L}"] = {"us_4_gemms_graph": round(us, 2), "TFLOPs": round(flops / us / 1e6, 1),
-                                          "plans": [pl.name + (f"/sk{pl.split_k}" if pl.split_k > 1 and pl.variant > 1 else "") for pl in plans]}
+                                          "plans": [pl.name + (f"/sk{pl.split_k}" if pl.split_k > 1 and pl.variant > 1 else "") for pl in plans],
+                                          "single_call_host_to_completion_us": _single_call_latency_us(
+                                              lambda: rt.dense(bufs[2][0], weights[2][0], weights[2][1], weights[2][4], out=bufs[2][1])),
+                                          "roofline": _roof("hbm", nbytes / us / 1e3, "GB/s", timing="the four launches replayed as a HIP "
+                                                            "graph", note="effective: 14 MB of weights stay cache-resident between replays"),
+                                          "roofline_mfma": _roof("mfma", flops / us / 1e6, "TFLOP/s")}
     return out
 
 
@@ -499,18 +574,42 @@ def cpu_baseline():
         t += time.perf_counter() - t0
         flops += 2.0 * M * (N1 * K1 + N2 * K2)
         del h, y
+    # the same oracle on one host thread (its OpenMP team is set to one thread through the OpenMP
+    # runtime the oracle library is linked against; the oracle itself is untouched): the first 768
+    # rows of the smallest draw, both GEMMs
+    single = None
+    try:
+        import ctypes
+        omp = ctypes.CDLL("libgomp.so.1")
+        threads = oracle.num_threads()
+        rows = 768
+        x = wl.activations(5, draws[0], int(Ms[draws[0]]), K1).f32[:rows]
+        omp.omp_set_num_threads(1)
+        try:
+            t0 = time.perf_counter()
+            h = oracle.dense(x, w1.f32, b1.f32, e1)
+            y = oracle.dense(h, w2.f32, b2.f32, e2)
+            t1 = time.perf_counter() - t0
+        finally:
+            omp.omp_set_num_threads(threads)
+        f1 = 2.0 * rows * (N1 * K1 + N2 * K2)
+        single = {"value": round(f1 / t1 / 1e12, 5), "unit": "TFLOP/s", "cores": 1,
+                  "sample": f"first {rows} rows of the smallest draw, FFN1+FFN2, {f1 / 1e9:.0f} GFLOP in {t1:.1f} s"}
+    except OSError:
+        pass
     return {"value": round(flops / t / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "sample": f"draws with M={[int(Ms[d]) for d in draws]} (smallest, quartiles, largest), "
-                                        f"FFN1+FFN2, {flops / 1e9:.0f} GFLOP in {t:.1f} s"}
+                                        f"FFN1+FFN2, {flops / 1e9:.0f} GFLOP in {t:.1f} s",
+            "single_thread": single}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # the first ~10 ms after idle run 10-13 % slower (clocks ramping up): the default warm-up is
-    # two passes over the 64 draws, the timed region eight passes
-    ap.add_argument("--steps", type=int, default=512)
-    ap.add_argument("--warmup", type=int, default=128)
+    # the timed loop runs `steps` steps REPEATS times (median reported) after an untimed pre-heat of
+    # fixed wall time and `warmup` further steps
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--extra-only", action="store_true",
@@ -552,6 +651,8 @@ def main():
                                "M = sum of 32 lengths U{1..512}, 64 seeded draws, one draw per step",
                    "mean_M": round(res["mean_M"], 1), "weights": "bf16 N(0,0.02)",
                    "activations": "bf16 U[-1,1)", "accumulate": "f32"},
+        "preheat_ms": res["preheat_ms"], "repeats": res["repeats"],
+        "ms_per_step_each_repeat": res["ms_per_step_each_repeat"],
         "roofline": res["roofline"],
     }
     if not args.no_extra:

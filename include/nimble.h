@@ -105,7 +105,8 @@ typedef struct nimble_plan {
   int64_t split_rows;     /* > 0: two launches.  Rows [0, split_rows), a whole number  */
                           /* of tiles (at most k*bm), run the r = 0 copy of `variant`; */
   int32_t residue_variant;/* the remaining rows run this variant in a second launch    */
-  int32_t reserved;
+  int32_t residue_split_k;/* ... with K cut into this many slices (workspace_bytes is   */
+                          /* the larger need of the two launches)                      */
 } nimble_plan;
 
 /* ----------------------------------------------------------------------------
@@ -130,6 +131,13 @@ int nimble_batch_matmul_shape(const int64_t* a_shape, int a_rank, const int64_t*
  * w (4H, Ix+H) -> h_out (B,H), c_out (B,H); all ranks 2. */
 int nimble_lstm_shape(const int64_t* x_shape, const int64_t* h_shape, const int64_t* c_shape,
                       const int64_t* w_shape, int64_t* h_out_shape, int64_t* c_out_shape);
+
+/* Shape function of the LSTM cell whose input share of the gates was computed beforehand
+ * (nimble_lstm_gates_pre_dyn): pre (B,4H), h (B,H), c (B,H), w_h (4H,H) -> h_out (B,H),
+ * c_out (B,H); all ranks 2.  Performs the run-time type check of that operator (Section 3.2):
+ * NIMBLE_ERR_SHAPE when the extents do not fit each other. */
+int nimble_lstm_pre_shape(const int64_t* pre_shape, const int64_t* h_shape, const int64_t* c_shape,
+                          const int64_t* wh_shape, int64_t* h_out_shape, int64_t* c_out_shape);
 
 /* Bytes of backing storage of a tensor (Section 3.3: alloc_storage(size,
  * alignment, device)): product of extents times the element size of `dtype`.
@@ -185,11 +193,12 @@ const char* nimble_last_error(void);
  * x [M,K] bf16, w [N,K] bf16, bias [N] bf16 (may be NULL for NIMBLE_EPI_NONE),
  * y [M,N] of out_dtype.  Accumulation and epilogue in f32.  The run-time type
  * check of the shape function is repeated (NIMBLE_ERR_SHAPE is impossible
- * here since one K is passed; negative extents give NIMBLE_ERR_ARG).
- * `force_variant` as in nimble_dense_plan. */
-int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
-                     int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
-                     void* workspace, size_t workspace_bytes, void* stream);
+ * here since one K is passed; negative extents give NIMBLE_ERR_ARG).  The dispatch function
+ * (Section 3.5) picks the kernel from the run-time M; it plans within `workspace_bytes` (no
+ * scratch: no K split). */
+int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M, int64_t N,
+                     int64_t K, int epilogue, int out_dtype, void* workspace, size_t workspace_bytes,
+                     void* stream);
 
 /* batch_matmul with dynamic M (and N or K when they are the same symbol):
  *   trans_b != 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,n,k]
@@ -222,7 +231,9 @@ int nimble_attention_dyn(const void* q, const void* k, const void* v, void* o, i
  *   h_out = sig(o) tanh(c_out).
  * x [B,Ix] bf16, h_prev [B,H] bf16, w [4H, Ix+H] bf16, bias [4H] bf16,
  * c_prev [B,H] f32, c_out [B,H] f32 (may alias c_prev), h_out [B,H] bf16 (must
- * not alias h_prev).  Ix and H must be multiples of 8. */
+ * not alias h_prev).  Ix and H must be multiples of 8.  w is read in its natural layout: the
+ * kernel gathers the four gate rows of a hidden unit itself, so there is no weight-packing pass
+ * (and no entry point for one). */
 int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, const void* bias,
                           const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t Ix,
                           int64_t H, void* workspace, size_t workspace_bytes, void* stream);
@@ -238,22 +249,6 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
 int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w_h,
                               const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t H,
                               void* stream);
-
-/* ----------------------------------------------------------------------------
- * Calibration probes: not part of the method.  The benchmark times them to print
- * what this GPU sustains next to the nominal peaks its roofline fractions use.
- * -------------------------------------------------------------------------- */
-
-/* Register-only bf16 MFMA loop: 256 workgroups of 4 * waves_per_simd waves (1, 2 or 4), each
- * wave issuing iters * 32 MFMAs of 16x16x32.  seed: device, 64 KiB of bf16 operand data (any
- * finite values); sink: device, 1 MiB, overwritten.  *flops receives the flop count of the
- * launch.  Asynchronous on `stream`; the caller times it. */
-int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int iters,
-                           double* flops, void* stream);
-
-/* Plain streaming read of `bytes` (a multiple of 16) from buf (device, 16-byte aligned).
- * sink: device, 16 bytes.  Asynchronous on `stream`; the caller times it. */
-int nimble_probe_hbm_read(const void* buf, size_t bytes, void* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -175,16 +175,27 @@ def lstm_step(x, h, w, b, c) -> Tuple[np.ndarray, np.ndarray]:
     return h_out, c_out
 
 
+def lstm_pre_shape(pre_shape, h_shape, c_shape, wh_shape):
+    """Shape function of the cell whose input share of the gates is given (Section 3.2, the
+    run-time type check): pre (B,4H), h (B,H), c (B,H), wh (4H,H) -> h' (B,H), c' (B,H)."""
+    shapes = [tuple(int(v) for v in s) for s in (pre_shape, h_shape, c_shape, wh_shape)]
+    if any(len(s) != 2 for s in shapes):
+        raise OracleShapeError("lstm_pre_shape: wrong rank")
+    if any(v < 0 for s in shapes for v in s):
+        raise ValueError("lstm_pre_shape: negative extent")
+    pre, h, c, wh = shapes
+    B, H = h
+    if pre != (B, 4 * H) or wh != (4 * H, H) or c != (B, H):
+        raise OracleShapeError("pre must be (B,4H), wh (4H,H), c (B,H)")
+    return (B, H), (B, H)
+
+
 def lstm_step_pre(pre, h, wh, c) -> Tuple[np.ndarray, np.ndarray]:
     """One LSTM cell step from gates whose input share pre = x.Wx^T + b [B, 4H] was computed
     beforehand (for all tokens in one product); wh [4H, H] are the recurrent columns of the
     fused weight.  Returns (h', c')."""
     pre, h, wh, c = _f(pre), _f(h), _f(wh), _f(c)
-    if h.ndim != 2 or pre.ndim != 2 or wh.ndim != 2 or c.ndim != 2:
-        raise OracleShapeError("rank-2 operands expected")
-    B, H = h.shape
-    if pre.shape != (B, 4 * H) or wh.shape != (4 * H, H) or c.shape != (B, H):
-        raise OracleShapeError("pre must be (B,4H), wh (4H,H), c (B,H)")
+    (B, H), _ = lstm_pre_shape(pre.shape, h.shape, c.shape, wh.shape)
     h_out = np.empty((B, H), dtype=np.float32)
     c_out = np.empty((B, H), dtype=np.float32)
     g = np.empty((B, 4 * H), dtype=np.float32)
@@ -232,6 +243,40 @@ def residue_split(x: int, tile: int) -> Tuple[int, int]:
     r = np.zeros(1, dtype=np.int64)
     _check(_load().oracle_residue_split(x, tile, _ip(k), _ip(r)), "residue_split")
     return int(k[0]), int(r[0])
+
+
+def maxnorm_rel_error(got, ref) -> float:
+    """max|got - ref| / max|ref| over one call's whole output (the infinity-norm companion of
+    normwise_rel_error, reported beside it); zero reference: 0 when got is zero too, else inf."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    den = float(np.max(np.abs(ref)))
+    num = float(np.max(np.abs(got - ref)))
+    if den == 0.0:
+        return 0.0 if num == 0.0 else float("inf")
+    return num / den
+
+
+def elementwise_excess(got, ref, rel: float, floor: float) -> float:
+    """Element-by-element gate beside the norms: the largest value over the output of
+    |got - ref| / (rel * |ref| + floor * rms(ref)), so a result <= 1 means every single element is
+    within rel of its reference value plus floor times the root mean square of the reference
+    (the absolute term covers elements that cancel to near zero).  A zero reference allows only
+    an exactly zero output (result 0, else inf)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    diff = np.abs(got - ref)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return 0.0 if float(np.max(diff)) == 0.0 else float("inf")
+    allowed = rel * np.abs(ref) + floor * rms
+    ratio = np.where(diff == 0.0, 0.0, diff / np.where(allowed > 0.0, allowed, 1.0))
+    ratio = np.where((allowed <= 0.0) & (diff > 0.0), np.inf, ratio)   # nothing allowed, something off
+    return float(np.max(ratio))
 
 
 def normwise_rel_error(got, ref) -> float:

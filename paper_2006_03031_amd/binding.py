@@ -10,7 +10,7 @@ from typing import Optional, Sequence, Tuple
 _PKG = os.path.dirname(os.path.abspath(__file__))
 # NIMBLE_LIBRARY names another build of the same library (for A/B measurements)
 _LIB_PATH = os.environ.get("NIMBLE_LIBRARY") or os.path.join(_PKG, "libnimble_hip.so")
-_HEADERS = [os.path.join(os.path.dirname(_PKG), "include", h) for h in ("nimble.h", "nimble_vm.h")]
+_HEADERS = [os.path.join(os.path.dirname(_PKG), "include", h) for h in ("nimble.h", "nimble_probe.h", "nimble_vm.h")]
 
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU_ERF = 0, 1, 2
 BF16, F32 = 0, 1
@@ -37,7 +37,7 @@ class _CPlan(ctypes.Structure):
                 ("residue_copy", ctypes.c_int32), ("split_k", ctypes.c_int32),
                 ("grid", ctypes.c_uint32 * 3), ("block", ctypes.c_uint32),
                 ("workspace_bytes", ctypes.c_uint64), ("split_rows", ctypes.c_int64),
-                ("residue_variant", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("residue_variant", ctypes.c_int32), ("residue_split_k", ctypes.c_int32)]
 
 
 @dataclass
@@ -56,6 +56,7 @@ class Plan:
     workspace_bytes: int
     split_rows: int = 0
     residue_variant: int = -1
+    residue_split_k: int = 0
 
 
 _lib = None
@@ -98,7 +99,9 @@ def load():
     lib.nimble_variant_name.argtypes = [i32]
     lib.nimble_variant_name.restype = ctypes.c_char_p
     lib.nimble_last_error.restype = ctypes.c_char_p
-    lib.nimble_dense_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.nimble_lstm_pre_shape.argtypes = [ip, ip, ip, ip, ip, ip]
+    lib.nimble_dense_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.nimble_dense_variant_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
     lib.nimble_batch_matmul_dyn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_float, i32, vp,
                                             ctypes.c_size_t, vp]
     lib.nimble_softmax_rows_dyn.argtypes = [vp, vp, i64, i64, vp]
@@ -186,6 +189,19 @@ def lstm_shape(x_shape, h_shape, c_shape, w_shape):
     return (ho[0], ho[1]), (co[0], co[1])
 
 
+def lstm_pre_shape(pre_shape, h_shape, c_shape, wh_shape):
+    for s in (pre_shape, h_shape, c_shape, wh_shape):
+        if len(s) != 2:
+            raise NimbleError(-2, "lstm expects rank-2 shapes")
+    ps, hs, cs, ws, ho, co = _SH2L
+    ps[0], ps[1] = pre_shape
+    hs[0], hs[1] = h_shape
+    cs[0], cs[1] = c_shape
+    ws[0], ws[1] = wh_shape
+    _check(load().nimble_lstm_pre_shape(ps, hs, cs, ws, ho, co))
+    return (ho[0], ho[1]), (co[0], co[1])
+
+
 def storage_bytes(shape: Sequence[int], dtype: int) -> int:
     if len(shape) == 2:
         arr = _SH2[2]
@@ -216,7 +232,7 @@ def variant_name(v: int) -> Optional[str]:
 def _plan(c: _CPlan) -> Plan:
     return Plan(c.variant, variant_name(c.variant) or "?", c.bm, c.bn, c.bk, c.k, c.r, c.residue_copy,
                 c.split_k, (c.grid[0], c.grid[1], c.grid[2]), c.block, c.workspace_bytes, c.split_rows,
-                c.residue_variant)
+                c.residue_variant, c.residue_split_k)
 
 
 def dense_plan(M: int, N: int, K: int, epilogue: int = EPI_BIAS, out_dtype: int = BF16,
@@ -250,10 +266,16 @@ def lstm_plan(B: int, Ix: int, H: int) -> Plan:
 # Pointers are integers (tensor.data_ptr()); `stream` is a hipStream_t handle as
 # an integer (torch.cuda.current_stream().cuda_stream), 0 for the default one.
 def nimble_dense_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,
-                     out_dtype: int = BF16, force_variant: int = VAR_AUTO, workspace: int = 0,
-                     workspace_bytes: int = 0, stream: int = 0) -> None:
-    _check(load().nimble_dense_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, force_variant, workspace,
-                                   workspace_bytes, stream))
+                     out_dtype: int = BF16, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
+    _check(load().nimble_dense_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, workspace, workspace_bytes, stream))
+
+
+def nimble_dense_variant_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,
+                             out_dtype: int = BF16, force_variant: int = VAR_AUTO, workspace: int = 0,
+                             workspace_bytes: int = 0, stream: int = 0) -> None:
+    """Measurement entry point: dense with the dispatch decision forced by the caller."""
+    _check(load().nimble_dense_variant_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, force_variant, workspace,
+                                           workspace_bytes, stream))
 
 
 def nimble_batch_matmul_dyn(a: int, b: int, c: int, batch: int, M: int, N: int, K: int, trans_b: bool,

@@ -25,8 +25,9 @@ __device__ __forceinline__ u16 f2bf(float f) {
   return (u16)(u >> 16);
 }
 
-// gelu(v) = v/2 (1 + erf(v / sqrt 2)), evaluated as v * sigmoid(a v + b v^3 + c v^5) with the
-// constants of fit_gelu_sigmoid.py (largest deviation from the erf form 2.5e-5, an order of
+// gelu(v) = v/2 (1 + erf(v / sqrt 2)), evaluated as v * sigmoid(a v + b v^3 + c v^5) with
+// a = 1.5950, b = 0.074011, c = -0.00070303 (a least-squares fit of the odd quintic to the erf form
+// on |v| <= 9, the constants below being -log2(e) times these; largest deviation 2.5e-5, an order of
 // magnitude below the bfloat16 spacing of the result; v^2 is clamped at 81, beyond which the
 // sigmoid is 0 or 1): seven ordinary instructions plus the hardware exp2 and reciprocal.  The
 // epilogue of a GELU layer is bound by exactly these instructions (128 outputs per lane with

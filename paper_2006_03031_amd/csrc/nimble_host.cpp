@@ -283,9 +283,14 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
   if (M * N > (1ll << 40)) return fail(NIMBLE_ERR_ARG, "output too large");
   int variant = force_variant;
   if (variant == NIMBLE_VAR_AUTO) {
-    const char* env = std::getenv("NIMBLE_FORCE_VARIANT");
-    if (env && *env) variant = std::atoi(env);
+    // measurement knob, read once: a force_variant value applied to every automatic plan
+    static const int env_variant = [] {
+      const char* env = std::getenv("NIMBLE_FORCE_VARIANT");
+      return (env && *env) ? std::atoi(env) : (int)NIMBLE_VAR_AUTO;
+    }();
+    variant = env_variant;
   }
+  const bool forced = variant != NIMBLE_VAR_AUTO;
   // a forced variant may carry a forced K split in bits 8..15 (NIMBLE_FORCE_SPLIT_K) and a
   // forced tile height in bits 16..23 (NIMBLE_FORCE_TILE_ROWS)
   int forced_sk = opt.force_split_k;
@@ -394,7 +399,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
                 kVariants[variant].name, tile_rows, (long long)N, (long long)K);
   if (tile_rows > 0 && tile_rows != kVariants[variant].bm && forced_sk > 1)
     return fail(NIMBLE_ERR_ARG, "a reduced tile height cannot be combined with a K split");
-  if (force_variant != NIMBLE_VAR_AUTO && forced_sk > 0) {
+  if (forced && forced_sk > 0) {
     if (!split_k_ok(variant, batch, N, K, forced_sk))
       return fail(NIMBLE_ERR_ARG, "variant %s cannot cut K=%lld into %d slices", kVariants[variant].name,
                   (long long)K, forced_sk);
@@ -405,11 +410,21 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
   }
   fill_tiled(p, variant, split_k, batch, split_rows > 0 ? split_rows : M, N, K, tile_rows);
   if (split_rows > 0) {
-    // k and r describe the whole call; grid and residue_copy describe the first launch
+    // k and r describe the whole call; grid and residue_copy describe the first launch; the second
+    // launch is planned here exactly as the entry point plans it, so that what is reported (its
+    // variant, its K split, the scratch the call needs) is what runs
+    PlanOptions tail_opt = opt;
+    tail_opt.allow_row_split = false;
+    nimble_plan tail;
+    const int rc = plan_dense(1, M - split_rows, N, K, epilogue, NIMBLE_VAR_AUTO, tail_opt, &tail);
+    if (rc != NIMBLE_OK) return rc;
     p->k = M / p->bm;
     p->r = (int32_t)(M % p->bm);
     p->split_rows = split_rows;
-    p->residue_variant = residue_variant;
+    p->residue_variant = tail.variant;
+    p->residue_split_k = tail.split_k;
+    if (tail.workspace_bytes > p->workspace_bytes) p->workspace_bytes = tail.workspace_bytes;
+    (void)residue_variant;
   }
   return NIMBLE_OK;
 }
@@ -478,6 +493,24 @@ int nimble_lstm_shape(const int64_t* x_shape, const int64_t* h_shape, const int6
   if (c_shape[1] != H) return fail(NIMBLE_ERR_SHAPE, "lstm: c is not (B,H)");
   if (w_shape[0] != 4 * H || w_shape[1] != Ix + H)
     return fail(NIMBLE_ERR_SHAPE, "lstm: w is not (4H, Ix+H)");
+  h_out_shape[0] = c_out_shape[0] = B;
+  h_out_shape[1] = c_out_shape[1] = H;
+  return NIMBLE_OK;
+}
+
+int nimble_lstm_pre_shape(const int64_t* pre_shape, const int64_t* h_shape, const int64_t* c_shape,
+                          const int64_t* wh_shape, int64_t* h_out_shape, int64_t* c_out_shape) {
+  clear_error();
+  if (!pre_shape || !h_shape || !c_shape || !wh_shape || !h_out_shape || !c_out_shape)
+    return fail(NIMBLE_ERR_NULL, "null shape pointer");
+  for (int i = 0; i < 2; ++i)
+    if (pre_shape[i] < 0 || h_shape[i] < 0 || c_shape[i] < 0 || wh_shape[i] < 0)
+      return fail(NIMBLE_ERR_ARG, "negative extent");
+  const int64_t B = h_shape[0], H = h_shape[1];
+  if (pre_shape[0] != B || c_shape[0] != B) return fail(NIMBLE_ERR_SHAPE, "lstm: batch extents differ");
+  if (pre_shape[1] != 4 * H) return fail(NIMBLE_ERR_SHAPE, "lstm: pre is not (B,4H)");
+  if (c_shape[1] != H) return fail(NIMBLE_ERR_SHAPE, "lstm: c is not (B,H)");
+  if (wh_shape[0] != 4 * H || wh_shape[1] != H) return fail(NIMBLE_ERR_SHAPE, "lstm: w_h is not (4H,H)");
   h_out_shape[0] = c_out_shape[0] = B;
   h_out_shape[1] = c_out_shape[1] = H;
   return NIMBLE_OK;
@@ -553,6 +586,11 @@ int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int
   clear_error();
   if (!plan) return fail(NIMBLE_ERR_NULL, "null plan");
   if (dtype_size(out_dtype) == 0) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  // batch_matmul is always one launch over all rows: no row split (its entry point launches the
+  // plan as it stands), no K split (no reduction pass for batches), no tuned dense table
+  PlanOptions bmm;
+  bmm.allow_row_split = false;
+  bmm.use_table = false;
   if (!trans_b) {
     // b is (T,K,N): its rows are not K-contiguous.  Where the tiled kernels could run the product
     // on b transposed (K a multiple of 8 and whole 16-byte batch strides), the plan is that NT
@@ -562,16 +600,16 @@ int nimble_batch_matmul_plan(int64_t batch, int64_t M, int64_t N, int64_t K, int
     // 0.35 us per million, 4 us at config 4's L = 128 and 70 us at L = 512)
     if (K > 0 && K % 8 == 0 && ((M * K) & 7) == 0 && ((N * K) & 7) == 0 && batch > 0 && M > 0 && N > 0 &&
         (double)batch * (double)M * (double)N * (double)K >= 32e6) {
-      int rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, PlanOptions(), plan);
+      int rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, bmm, plan);
       if (rc != NIMBLE_OK) return rc;
       if (plan->variant >= NIMBLE_VAR_T32x128) {
         plan->workspace_bytes = (uint64_t)batch * (uint64_t)N * (uint64_t)K * 2u;
         return NIMBLE_OK;
       }
     }
-    return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), plan);
+    return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, bmm, plan);
   }
-  return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, PlanOptions(), plan);
+  return plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_AUTO, bmm, plan);
 }
 
 int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {

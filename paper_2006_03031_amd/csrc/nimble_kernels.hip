@@ -31,6 +31,7 @@
 #include "gemm_tile_kernel.h"
 #include "misc_kernels.h"
 #include "nimble_internal.h"
+#include "nimble_probe.h"
 #include "probe_kernels.h"
 #include "skinny_kernel.h"
 
@@ -49,11 +50,14 @@ static int check_hip(hipError_t e, const char* what) {
 template <int BM, int BN, int WGM, int WGN, int WS = 2, int S = 4>
 static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  int group_m = 4;  // measured best of 1..32 on the BERT-large FFN shapes
-  if (const char* env = std::getenv("NIMBLE_GROUP_M")) {  // tuning knob: tile rows per L2 group
-    const int v = std::atoi(env);
-    if (v > 0) group_m = v;
-  }
+  // tile rows per L2 group: 4 measured best of 1..32 on the BERT-large FFN shapes (NIMBLE_GROUP_M is a
+  // tuning knob, read once)
+  static const int group_m_default = [] {
+    const char* env = std::getenv("NIMBLE_GROUP_M");
+    const int v = env ? std::atoi(env) : 0;
+    return v > 0 ? v : 4;
+  }();
+  int group_m = group_m_default;
   if (group_m > tiles_m) group_m = tiles_m;
   const int slices = p.split_k > 1 ? p.split_k : 1;
   // at most as many workgroups as are resident at once (one per compute unit for the 8-wave
@@ -126,6 +130,7 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
       s.K = g.K;
       s.epilogue = g.epilogue;
       s.out_f32 = g.out_f32;
+      s.alpha = g.alpha;
       return launch_skinny<false>(s, p, st);
     }
     case NIMBLE_VAR_T32x128: return launch_ring<32, 128, 1, 2, 3>(g, p, st);
@@ -175,9 +180,16 @@ static int run_dense(const GemmArgs& g, const nimble_plan& p, void* workspace, h
   return check_hip(hipGetLastError(), "split-K reduction launch");
 }
 
-int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
-                     int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M, int64_t N,
+                     int64_t K, int epilogue, int out_dtype, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  return nimble_dense_variant_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, NIMBLE_VAR_AUTO, workspace,
+                                  workspace_bytes, stream);
+}
+
+int nimble_dense_variant_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
+                             int64_t N, int64_t K, int epilogue, int out_dtype, int force_variant,
+                             void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   if (M < 0 || N < 0 || K < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
@@ -292,6 +304,9 @@ int nimble_batch_matmul_dyn(const void* a, const void* b, void* c, int64_t batch
     rc = plan_dense(batch, M, N, K, NIMBLE_EPI_NONE, NIMBLE_VAR_GENERIC, PlanOptions(), &p);
     if (rc != NIMBLE_OK) return rc;
   }
+  // one launch over all rows: a plan that splits rows or K would run the r = 0 copy past M
+  if (p.split_rows != 0 || (p.split_k > 1 && p.variant >= NIMBLE_VAR_T32x128))
+    return fail(NIMBLE_ERR_ARG, "batch_matmul plan is not a single launch");
   return launch_gemm(g, p, (hipStream_t)stream);
 }
 
@@ -356,6 +371,7 @@ int nimble_lstm_gates_dyn(const void* x, const void* h_prev, const void* w, cons
   s.Ix = (int)Ix;
   s.H = (int)H;
   s.epilogue = NIMBLE_EPI_BIAS;
+  s.alpha = 1.0f;
   return launch_skinny<true>(s, p, (hipStream_t)stream);
 }
 
@@ -384,6 +400,7 @@ int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w
   s.Ix = 0;
   s.H = (int)H;
   s.epilogue = NIMBLE_EPI_BIAS;
+  s.alpha = 1.0f;
   return launch_skinny<true>(s, p, (hipStream_t)stream);
 }
 

@@ -364,8 +364,7 @@ int invoke_packed(Frame& f, int id, const int64_t* r) {
       const int epi = id == NIMBLE_PF_DENSE ? NIMBLE_EPI_NONE
                       : id == NIMBLE_PF_DENSE_BIAS ? NIMBLE_EPI_BIAS : NIMBLE_EPI_BIAS_GELU_ERF;
       return nimble_dense_dyn(x->data, w->data, b ? b->data : nullptr, y->data, out[0], out[1],
-                              x->shape[1], epi, y->dtype, NIMBLE_VAR_AUTO, vm->workspace,
-                              vm->workspace_bytes, vm->stream);
+                              x->shape[1], epi, y->dtype, vm->workspace, vm->workspace_bytes, vm->stream);
     }
     case NIMBLE_PF_LSTM_GATES: {
       Object* t[7];

@@ -26,6 +26,7 @@ struct SkinnyArgs {
   int M, N, K;      // LSTM: M = B, N = 4H, K = Ix + H
   int Ix, H;        // LSTM only
   int epilogue, out_f32;
+  float alpha;      // scale of the product (dense and LSTM: 1; batch_matmul with one batch: its alpha)
 };
 
 // U = 32-wide k steps whose loads a wave issues together before it multiplies.  8 keeps four
@@ -171,7 +172,7 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
         if (m < M) {
           const float sum = (red[0][t][mm][nn] + red[1][t][mm][nn]) +
                             (red[2][t][mm][nn] + red[3][t][mm][nn]);
-          const float v = epilogue(sum, 1.0f, b, s.epilogue);
+          const float v = epilogue(sum, s.alpha, b, s.epilogue);
           const long long o = (long long)m * N + n;
           if (s.out_f32)
             ((float*)s.y)[o] = v;

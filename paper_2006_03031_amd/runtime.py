@@ -73,6 +73,20 @@ def default_workspace(device) -> torch.Tensor:
     return ws
 
 
+def _ptr(t: torch.Tensor, dtype, what: str) -> int:
+    """Device address of a tensor the C ABI can take as a plain pointer: contiguous, on the GPU and
+    of the element type the entry point reads; anything else is refused here (the library sees only
+    an address and would read a strided view or another dtype as packed data)."""
+    if t.dtype is not dtype or not t.is_cuda or not t.is_contiguous():
+        raise nb.NimbleError(-4 if t.dtype is not dtype else -8,
+                             f"{what}: need a contiguous {dtype} tensor on the GPU, got {t.dtype}, "
+                             f"device {t.device}, strides {tuple(t.stride())}")
+    return t.data_ptr()
+
+
+_BF, _F32 = torch.bfloat16, torch.float32
+
+
 def _alloc(shape, dtype: int, device) -> torch.Tensor:
     # alloc_storage(size, alignment, device) + alloc_tensor(storage, 0, shape, dtype):
     # torch's caching allocator returns storage aligned to at least 512 bytes.
@@ -88,14 +102,24 @@ def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], epilog
     K = x.shape[1]
     if out is not None:
         y = out
+        if tuple(y.shape) != (M, N):
+            raise nb.NimbleError(-3, f"dense: out is {tuple(y.shape)}, the shape function gives {(M, N)}")
     elif arena is not None:
         y = arena.alloc((M, N), out_dtype)
     else:
         y = _alloc((M, N), out_dtype, x.device)
     ws = workspace if workspace is not None else default_workspace(x.device)
-    nb.nimble_dense_dyn(x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else 0,
-                        y.data_ptr(), M, N, K, epilogue, out_dtype, force_variant, ws.data_ptr(),
-                        ws.numel() * ws.element_size(), _stream())
+    px, pw = _ptr(x, _BF, "x"), _ptr(w, _BF, "w")
+    pb = _ptr(bias, _BF, "bias") if bias is not None else 0
+    if bias is not None and bias.numel() != N:
+        raise nb.NimbleError(-3, f"dense: bias has {bias.numel()} elements, N is {N}")
+    py = _ptr(y, _TORCH_DTYPE[out_dtype], "y")
+    if force_variant == nb.VAR_AUTO:
+        nb.nimble_dense_dyn(px, pw, pb, py, M, N, K, epilogue, out_dtype, ws.data_ptr(),
+                            ws.numel() * ws.element_size(), _stream())
+    else:   # ablation, tuning and the per-variant tests pin one member of the kernel family
+        nb.nimble_dense_variant_dyn(px, pw, pb, py, M, N, K, epilogue, out_dtype, force_variant, ws.data_ptr(),
+                                    ws.numel() * ws.element_size(), _stream())
     return y
 
 
@@ -106,8 +130,8 @@ def batch_matmul(a: torch.Tensor, b: torch.Tensor, trans_b: bool, alpha: float =
     K = a.shape[2]
     c = out if out is not None else _alloc((T, M, N), out_dtype, a.device)
     ws = workspace if workspace is not None else default_workspace(a.device)   # b transposed, for the NN product
-    nb.nimble_batch_matmul_dyn(a.data_ptr(), b.data_ptr(), c.data_ptr(), T, M, N, K, trans_b, alpha,
-                               out_dtype, ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
+    nb.nimble_batch_matmul_dyn(_ptr(a, _BF, "a"), _ptr(b, _BF, "b"), _ptr(c, _TORCH_DTYPE[out_dtype], "c"), T, M, N, K,
+                               trans_b, alpha, out_dtype, ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
     return c
 
 
@@ -115,7 +139,7 @@ def softmax_rows(s: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.T
     cols = s.shape[-1]
     rows = s.numel() // cols if cols else 0
     p = out if out is not None else _alloc(tuple(s.shape), nb.BF16, s.device)
-    nb.nimble_softmax_rows_dyn(s.data_ptr(), p.data_ptr(), rows, cols, _stream())
+    nb.nimble_softmax_rows_dyn(_ptr(s, _F32, "s"), _ptr(p, _BF, "p"), rows, cols, _stream())
     return p
 
 
@@ -135,7 +159,8 @@ def fused_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, alpha: fl
     s_shape = nb.batch_matmul_shape(tuple(q.shape), tuple(k.shape), True)
     T, L, D = nb.batch_matmul_shape(s_shape, tuple(v.shape), False)
     o = out if out is not None else _alloc((T, L, D), nb.BF16, q.device)
-    nb.nimble_attention_dyn(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), T, L, D, alpha, _stream())
+    nb.nimble_attention_dyn(_ptr(q, _BF, "q"), _ptr(k, _BF, "k"), _ptr(v, _BF, "v"), _ptr(o, _BF, "o"), T, L, D, alpha,
+                            _stream())
     return o
 
 
@@ -148,8 +173,9 @@ def lstm_step(x: torch.Tensor, h: torch.Tensor, w: torch.Tensor, bias: torch.Ten
         h_out = _alloc((B, H), nb.BF16, x.device)
     if c_out is None:
         c_out = _alloc((B, H), nb.F32, x.device)
-    nb.nimble_lstm_gates_dyn(x.data_ptr(), h.data_ptr(), w.data_ptr(), bias.data_ptr(), c.data_ptr(),
-                             c_out.data_ptr(), h_out.data_ptr(), B, Ix, H, 0, 0, _stream())
+    nb.nimble_lstm_gates_dyn(_ptr(x, _BF, "x"), _ptr(h, _BF, "h"), _ptr(w, _BF, "w"), _ptr(bias, _BF, "bias"),
+                             _ptr(c, _F32, "c"), _ptr(c_out, _F32, "c_out"), _ptr(h_out, _BF, "h_out"), B, Ix, H, 0, 0,
+                             _stream())
     return h_out, c_out
 
 
@@ -157,16 +183,13 @@ def lstm_step_pre(pre: torch.Tensor, h: torch.Tensor, w_h: torch.Tensor, c: torc
                   h_out: Optional[torch.Tensor] = None,
                   c_out: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """One cell step from the precomputed input share of the gates pre [B, 4H] (f32)."""
-    B, H = h.shape
-    if tuple(pre.shape) != (B, 4 * H) or tuple(w_h.shape) != (4 * H, H) or tuple(c.shape) != (B, H):
-        raise nb.NimbleError(-3, f"lstm_step_pre: pre {tuple(pre.shape)}, w_h {tuple(w_h.shape)}, c {tuple(c.shape)} "
-                                 f"do not fit h {tuple(h.shape)}")
+    (B, H), _ = nb.lstm_pre_shape(tuple(pre.shape), tuple(h.shape), tuple(c.shape), tuple(w_h.shape))
     if h_out is None:
         h_out = _alloc((B, H), nb.BF16, h.device)
     if c_out is None:
         c_out = _alloc((B, H), nb.F32, h.device)
-    nb.nimble_lstm_gates_pre_dyn(pre.data_ptr(), h.data_ptr(), w_h.data_ptr(), c.data_ptr(), c_out.data_ptr(),
-                                 h_out.data_ptr(), B, H, _stream())
+    nb.nimble_lstm_gates_pre_dyn(_ptr(pre, _F32, "pre"), _ptr(h, _BF, "h"), _ptr(w_h, _BF, "w_h"), _ptr(c, _F32, "c"),
+                                 _ptr(c_out, _F32, "c_out"), _ptr(h_out, _BF, "h_out"), B, H, _stream())
     return h_out, c_out
 
 

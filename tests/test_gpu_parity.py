@@ -1,7 +1,12 @@
 """Parity of the HIP path with the CPU oracle, element by element, on the same
 seeded bf16-rounded inputs.  Bar: max normwise relative error 5e-3 per call
-(||gpu - ref||_F / ||ref||_F over the call's whole output); shape outputs
-bit-exact."""
+(||gpu - ref||_F / ||ref||_F over the call's whole output) AND, for every single
+element, |gpu - ref| <= rel |ref| + floor rms(ref) with rel = floor = 2^-7 for
+bf16 outputs (four times the 2^-9 half-ulp of a correctly rounded result; the
+rms term covers elements that cancel to near zero), 2^-14 for f32 outputs
+(summation order only), 2^-11 for f32 outputs behind the GELU epilogue (whose
+fitted form deviates by up to 2.5e-5 from the erf form); shape outputs bit-exact.
+The largest max|d| / max|ref| seen per test is printed (run with -s)."""
 import numpy as np
 import pytest
 
@@ -39,6 +44,35 @@ def _err(got, ref):
     return oracle.normwise_rel_error(got, ref)
 
 
+GATE_BF16 = 2.0 ** -7
+GATE_F32 = 2.0 ** -14
+GATE_F32_GELU = 2.0 ** -11
+_worst = {"fro": 0.0, "inf": 0.0, "elem": 0.0}
+
+
+def _check(got, ref, what=None, f32=False, gelu=False, floor=None):
+    """The parity gate of one call: the Frobenius ratio within 5e-3 and every element within the
+    element-wise bound (see the module docstring); returns the Frobenius ratio."""
+    rel = (GATE_F32_GELU if gelu else GATE_F32) if f32 else GATE_BF16
+    e = oracle.normwise_rel_error(got, ref)
+    assert e <= TOL, ("normwise", what, e)
+    x = oracle.elementwise_excess(got, ref, rel, rel if floor is None else floor)
+    assert x <= 1.0, ("element-wise", what, x, rel)
+    _worst["fro"] = max(_worst["fro"], e)
+    _worst["inf"] = max(_worst["inf"], oracle.maxnorm_rel_error(got, ref))
+    _worst["elem"] = max(_worst["elem"], x)
+    return e
+
+
+@pytest.fixture(autouse=True)
+def _report_worst(request):
+    _worst.update(fro=0.0, inf=0.0, elem=0.0)
+    yield
+    if _worst["fro"] > 0.0:
+        print(f"\n[{request.node.name}] worst ||d||_F/||ref||_F = {_worst['fro']:.3e}, "
+              f"max|d|/max|ref| = {_worst['inf']:.3e}, element-wise bound used up to {_worst['elem']:.2f}")
+
+
 # ------------------------------------------------------------------ config 1
 def test_config1_all_64_calls(rt, nb):
     to_dev, _, from_dev, _ = _dev()
@@ -50,7 +84,7 @@ def test_config1_all_64_calls(rt, nb):
         y = rt.dense(x, w, b, nb.EPI_BIAS)
         assert tuple(y.shape) == oracle.dense_shape(c.x.shape, c.w.shape)
         ref = oracle.dense(c.x.f32, c.w.f32, c.b.f32, "bias")
-        worst = max(worst, _err(from_dev(y), ref))
+        worst = max(worst, _check(from_dev(y), ref, ("config1", c.M)))
     assert worst <= TOL, worst
 
 
@@ -74,8 +108,7 @@ def _sweep(rt, nb, variant, N, K, Ms, epilogue="bias_gelu", out_dtype=0, seed=0)
         rt.dense(xd[:M], wd, bd, EPI[epilogue], out_dtype, variant, out=buf[:M])
         got = from_dev(buf)
         assert np.all(got[M:] == 768.0), f"variant {variant} wrote past row M={M}"
-        e = _err(got[:M], ref[:M])
-        assert e <= TOL, (variant, M, N, K, e)
+        e = _check(got[:M], ref[:M], (variant, M, N, K, epilogue), f32=out_dtype == 1, gelu=epilogue == "bias_gelu")
         worst = max(worst, e)
     return worst
 
@@ -124,7 +157,7 @@ def test_auto_dispatch_picks_a_tile_height_that_fills_the_rounds(rt, nb):
         y = rt.dense(to_dev(x), to_dev(w), to_dev(b), EPI[epi])
         rows = np.r_[0:3, M // 2:M // 2 + 3, M - 260:M]   # sampled rows, the last tile row included
         ref = oracle.dense(x.f32[rows], w.f32, b.f32, epi)
-        assert _err(from_dev(y)[rows], ref) <= TOL, (M, N, K)
+        _check(from_dev(y)[rows], ref, (M, N, K))
 
 
 @pytest.mark.parametrize("variant", sorted(TILED))
@@ -173,7 +206,8 @@ def test_random_shapes_through_the_dispatch_function(rt, nb):
         y = rt.dense(to_dev(x), to_dev(w), to_dev(b) if epi != "none" else None, EPI[epi], out_dtype)
         ref = oracle.dense(x.f32, w.f32, b.f32 if epi != "none" else None, epi)
         assert tuple(y.shape) == (M, N)
-        assert _err(from_dev(y), ref) <= TOL, (case, M, N, K, epi, out_dtype, p.name, p.split_k)
+        _check(from_dev(y), ref, (case, M, N, K, epi, out_dtype, p.name, p.split_k), f32=out_dtype == 1,
+               gelu=epi == "bias_gelu")
     assert len({name for name, _, _ in seen}) >= 4, seen   # the draw reaches several kernels
 
 
@@ -195,7 +229,7 @@ def test_split_k_forced_and_auto(rt, nb):
     rng = np.random.default_rng(77)
     x, w, b = wl.uniform_bf16(rng, (300, 3072)), wl.normal_bf16(rng, (768, 3072)), wl.uniform_bf16(rng, (768,))
     y = rt.dense(to_dev(x), to_dev(w), to_dev(b), nb.EPI_BIAS, workspace=empty)
-    assert _err(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias")) <= TOL
+    _check(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias"), "no workspace")
     with pytest.raises(nb.NimbleError) as e:  # a forced split that does not fit is refused, not shrunk
         rt.dense(to_dev(x), to_dev(w), to_dev(b), nb.EPI_BIAS, force_variant=4 | (4 << 8), workspace=empty)
     assert e.value.code == -6
@@ -276,9 +310,34 @@ def test_two_requests_in_flight_on_two_streams(rt, nb):
 
 
 # ------------------------------------------------------------------ config 3
-def test_config3_bert_base_gemms(rt, nb):
+@pytest.mark.parametrize("gemm", range(4))
+def test_config3_bert_base_gemms_every_length(rt, nb, gemm):
+    """Each BERT-base GEMM at every sequence length L = 1..512 through the dispatch function (weight
+    streaming, every small tile, K splits): one oracle evaluation at 512 rows serves every L by
+    row-prefix invariance; each call is gated on its own and its guard rows must stay untouched."""
     to_dev, _, from_dev, _ = _dev()
-    Ls = sorted(set([1, 512] + [int(v) for v in wl.config3_lengths()[:6]]))
+    name, K, N, epi = wl.BERT_BASE_GEMMS[gemm]
+    w, b = wl.dense_weights(3, gemm, N, K)
+    x = wl.activations(3, 500 + gemm, 512, K)
+    ref = oracle.dense(x.f32, w.f32, b.f32, epi)
+    xd, wd, bd = to_dev(x), to_dev(w), to_dev(b)
+    buf = torch.empty((512 + 2, N), dtype=torch.bfloat16, device="cuda")
+    names = set()
+    for L in range(1, 513):
+        buf.fill_(768.0)
+        y = rt.dense(xd[:L], wd, bd, EPI[epi], out=buf[:L])
+        assert tuple(y.shape) == oracle.dense_shape((L, K), (N, K))
+        got = from_dev(buf)
+        assert np.all(got[L:] == 768.0), (name, L)
+        _check(got[:L], ref[:L], (name, L), gelu=epi == "bias_gelu")
+        names.add(nb.dense_plan(L, N, K, EPI[epi]).name)
+    assert len(names) >= 2, names
+
+
+def test_config3_the_drawn_lengths_with_their_own_inputs(rt, nb):
+    """The config's own draws (L ~ U{1..512}, fresh activations per draw and GEMM), all four GEMMs."""
+    to_dev, _, from_dev, _ = _dev()
+    Ls = [int(v) for v in wl.config3_lengths()[:24]]
     weights = [wl.dense_weights(3, i, N, K) for i, (_, K, N, _) in enumerate(wl.BERT_BASE_GEMMS)]
     dweights = [(to_dev(w), to_dev(b)) for w, b in weights]
     for d, L in enumerate(Ls):
@@ -287,8 +346,7 @@ def test_config3_bert_base_gemms(rt, nb):
             y = rt.dense(to_dev(x), dweights[i][0], dweights[i][1], EPI[epi])
             assert tuple(y.shape) == (L, N)
             ref = oracle.dense(x.f32, weights[i][0].f32, weights[i][1].f32, epi)
-            e = _err(from_dev(y), ref)
-            assert e <= TOL, (name, L, e)
+            _check(from_dev(y), ref, (name, L), gelu=epi == "bias_gelu")
 
 
 # ------------------------------------------------------------------ config 5
@@ -300,12 +358,14 @@ def _sampled_rows(M, bm_max, n_random, rng):
 
 def test_config5_ragged_ffn_sampled_rows(rt, nb):
     """Full-size M (sum of 32 lengths) in the launch configuration the benchmark
-    times; the oracle evaluates the residue region (last 512 rows) plus random
-    rows, which row independence makes exact.  FFN2 is teacher-forced with the
+    times (outputs carved from one storage arena), all 64 draws; the oracle evaluates the
+    residue region (the last 320 rows: the tallest tile) plus random rows, which row
+    independence makes exact.  FFN2 is teacher-forced with the
     GPU's own bf16 FFN1 output."""
     to_dev, _, from_dev, _ = _dev()
     Ms = wl.config5_token_counts()
-    draws = [int(np.argmin(Ms)), int(np.argsort(Ms)[len(Ms) // 2]), int(np.argmax(Ms))]
+    draws = range(len(Ms))       # all 64 draws
+    arena = rt.StorageArena(int(max(Ms)) * (4096 + 1024) * 2 + 4096)   # outputs carved as the benchmark does
     (n1, K1, N1, e1), (n2, K2, N2, e2) = wl.BERT_LARGE_FFN
     w1, b1 = wl.dense_weights(5, 0, N1, K1)
     w2, b2 = wl.dense_weights(5, 1, N2, K2)
@@ -314,15 +374,17 @@ def test_config5_ragged_ffn_sampled_rows(rt, nb):
     for d in draws:
         M = int(Ms[d])
         x = wl.activations(5, d, M, K1)
-        h = rt.dense(to_dev(x), dw1, db1, EPI[e1])
-        y = rt.dense(h, dw2, db2, EPI[e2])
+        arena.reset()
+        h = rt.dense(to_dev(x), dw1, db1, EPI[e1], arena=arena)
+        y = rt.dense(h, dw2, db2, EPI[e2], arena=arena)
         assert tuple(h.shape) == (M, N1) and tuple(y.shape) == (M, N2)
-        rows = _sampled_rows(M, 256, 96, rng)
+        assert y.data_ptr() >= h.data_ptr() + M * N1 * 2      # two tensors of one storage, not overlapping
+        rows = _sampled_rows(M, 160, 64, rng)
         hg = from_dev(h)
         ref_h = oracle.dense(x.f32[rows], w1.f32, b1.f32, e1)
-        assert _err(hg[rows], ref_h) <= TOL, ("ffn1", M)
+        _check(hg[rows], ref_h, ("ffn1", M), gelu=True)
         ref_y = oracle.dense(hg[rows], w2.f32, b2.f32, e2)
-        assert _err(from_dev(y)[rows], ref_y) <= TOL, ("ffn2", M)
+        _check(from_dev(y)[rows], ref_y, ("ffn2", M))
 
 
 def test_config5_fixed_sizes_up_to_the_maximum(rt, nb):
@@ -341,8 +403,8 @@ def test_config5_fixed_sizes_up_to_the_maximum(rt, nb):
         y = rt.dense(h, dw2, db2, EPI[e2])
         rows = _sampled_rows(M, 160, 64, rng)
         hg = from_dev(h)
-        assert _err(hg[rows], oracle.dense(x.f32[rows], w1.f32, b1.f32, e1)) <= TOL, ("ffn1", M)
-        assert _err(from_dev(y)[rows], oracle.dense(hg[rows], w2.f32, b2.f32, e2)) <= TOL, ("ffn2", M)
+        _check(hg[rows], oracle.dense(x.f32[rows], w1.f32, b1.f32, e1), ("ffn1", M))
+        _check(from_dev(y)[rows], oracle.dense(hg[rows], w2.f32, b2.f32, e2), ("ffn2", M))
 
 
 def test_config5_residue_sweep_2048_plus_r(rt, nb):
@@ -365,12 +427,12 @@ def test_config5_residue_sweep_2048_plus_r(rt, nb):
         rows = rows_all[rows_all < M]
         idx = [pos[int(v)] for v in rows]
         hg = from_dev(h)
-        assert _err(hg[rows], ref_h_all[idx]) <= TOL, ("ffn1", M)
+        _check(hg[rows], ref_h_all[idx], ("ffn1", M))
         if r % 16 in (0, 1, 15):  # FFN2 needs a fresh oracle evaluation per M (teacher forcing)
             y = rt.dense(h, dw2, db2, EPI[e2])
             sub = rows[-40:]
             ref_y = oracle.dense(hg[sub], w2.f32, b2.f32, e2)
-            assert _err(from_dev(y)[sub], ref_y) <= TOL, ("ffn2", M)
+            _check(from_dev(y)[sub], ref_y, ("ffn2", M))
 
 
 # ------------------------------------------------------------------ config 2
@@ -392,9 +454,48 @@ def test_lstm_teacher_forced_steps(rt, nb):
             h2, c2 = rt.lstm_step(to_dev(xt), h, dw, db, c)
             assert tuple(h2.shape) == (B, H) and tuple(c2.shape) == (B, H)
             ref_h, ref_c = oracle.lstm_step(xt.f32, h_in, lw.w.f32, lw.b.f32, c_in)
-            assert _err(from_dev(c2), ref_c) <= TOL, ("c", B, t)
-            assert _err(from_dev(h2), ref_h) <= TOL, ("h", B, t)
+            _check(from_dev(c2), ref_c, ("c", B, t), f32=True)
+            _check(from_dev(h2), ref_h, ("h", B, t))
             h, c = h2, c2
+
+
+def test_lstm_one_step_at_every_batch_size(rt, nb):
+    """Config 2's cell (2048 x 1024) at every dynamic batch B = 1..64 (every residue of the 16-row
+    tile, every row-block split the dispatch function makes), the fused cell and the cell with the
+    inputs' share precomputed; h and c arbitrary (not the zero start), guard rows untouched."""
+    to_dev, f32_to_dev, from_dev, _ = _dev()
+    lw = wl.config2_weights()
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    H, Ix = wl.LSTM_H, wl.LSTM_IX
+    w_x, w_h = rt.split_lstm_weight(dw, Ix)
+    wh_ref = np.ascontiguousarray(lw.w.f32[:, Ix:])
+    rng = np.random.default_rng(64)
+    x_all, h_all = wl.uniform_bf16(rng, (64, Ix)), wl.uniform_bf16(rng, (64, H))
+    c_all = (2.0 * rng.random((64, H)) - 1.0).astype(np.float32)
+    xd, hd, cd = to_dev(x_all), to_dev(h_all), f32_to_dev(c_all)
+    pre_all = rt.dense(xd, w_x, db, nb.EPI_BIAS, nb.F32)
+    pre_np = from_dev(pre_all)
+    blocks = set()
+    for B in range(1, 65):
+        blocks.add(nb.lstm_plan(B, Ix, H).grid[1])
+        ref_h, ref_c = oracle.lstm_step(x_all.f32[:B], h_all.f32[:B], lw.w.f32, lw.b.f32, c_all[:B])
+        hb = torch.full((B + 1, H), 768.0, dtype=torch.bfloat16, device="cuda")
+        cb = torch.full((B + 1, H), 768.0, dtype=torch.float32, device="cuda")
+        h2, c2 = rt.lstm_step(xd[:B], hd[:B], dw, db, cd[:B], h_out=hb[:B], c_out=cb[:B])
+        hg, cg = from_dev(hb), from_dev(cb)
+        assert np.all(hg[B:] == 768.0) and np.all(cg[B:] == 768.0), B
+        _check(cg[:B], ref_c, ("c", B), f32=True)
+        _check(hg[:B], ref_h, ("h", B))
+        hb.fill_(768.0)
+        cb.fill_(768.0)
+        rt.lstm_step_pre(pre_all[:B], hd[:B], w_h, cd[:B], h_out=hb[:B], c_out=cb[:B])
+        hg, cg = from_dev(hb), from_dev(cb)
+        assert np.all(hg[B:] == 768.0) and np.all(cg[B:] == 768.0), B
+        rh, rc = oracle.lstm_step_pre(pre_np[:B], h_all.f32[:B], wh_ref, c_all[:B])
+        _check(cg[:B], rc, ("c pre", B), f32=True)
+        _check(hg[:B], rh, ("h pre", B))
+        _check(hg[:B], ref_h, ("h pre vs fused oracle", B))
+    assert blocks == {1, 2}, blocks
 
 
 def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
@@ -431,7 +532,8 @@ def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
         xdev = to_dev(xx) if Ix2 else torch.zeros((B2, 0), dtype=torch.bfloat16, device="cuda")
         hg, cg = rt.lstm_step(xdev, to_dev(hh), to_dev(ww), to_dev(bias), f32_to_dev(cc))
         rh, rc = oracle.lstm_step(xx.f32.reshape(B2, Ix2), hh.f32, ww.f32, bias.f32, cc)
-        assert _err(from_dev(cg), rc) <= TOL and _err(from_dev(hg), rh) <= TOL, (B2, H2, Ix2)
+        _check(from_dev(cg), rc, ("c", B2, H2, Ix2), f32=True)
+        _check(from_dev(hg), rh, ("h", B2, H2, Ix2))
 
 
 def test_lstm_sequence_graph_replays_match_eager(rt, nb):
@@ -462,7 +564,7 @@ def test_lstm_sequence_graph_replays_match_eager(rt, nb):
         x0 = wl.BF16Array(xs.bits[0], xs.f32[0])
         rh, rc = oracle.lstm_step(x0.f32, np.zeros((B, H), np.float32), lw.w.f32, lw.b.f32,
                                   np.zeros((B, H), np.float32))
-        assert _err(from_dev(hs[0]), rh) <= TOL
+        _check(from_dev(hs[0]), rh, ("graph step 0", B))
 
 
 def test_lstm_from_precomputed_input_gates(rt, nb):
@@ -479,7 +581,7 @@ def test_lstm_from_precomputed_input_gates(rt, nb):
         xd = to_dev(xs)
         pre = rt.dense(xd.view(steps * B, Ix), w_x, db, nb.EPI_BIAS, nb.F32).view(steps, B, 4 * H)
         pre_ref = oracle.dense(xs.f32.reshape(steps * B, Ix), wx_ref, lw.b.f32, "bias")
-        assert _err(from_dev(pre).reshape(steps * B, 4 * H), pre_ref) <= TOL, ("pre", B)
+        _check(from_dev(pre).reshape(steps * B, 4 * H), pre_ref, ("pre", B), f32=True)
         pre_np = from_dev(pre)
         h = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
         c = torch.zeros((B, H), dtype=torch.float32, device="cuda")
@@ -487,11 +589,11 @@ def test_lstm_from_precomputed_input_gates(rt, nb):
             h_in, c_in = from_dev(h), from_dev(c)
             h2, c2 = rt.lstm_step_pre(pre[t], h, w_h, c)
             ref_h, ref_c = oracle.lstm_step_pre(pre_np[t], h_in, wh_ref, c_in)
-            assert _err(from_dev(c2), ref_c) <= TOL, ("c", B, t)
-            assert _err(from_dev(h2), ref_h) <= TOL, ("h", B, t)
+            _check(from_dev(c2), ref_c, ("c", B, t), f32=True)
+            _check(from_dev(h2), ref_h, ("h", B, t))
             # and against the fused cell of the oracle on the original inputs (pre is exact up to f32 order)
             fh, fc = oracle.lstm_step(xs.f32[t], h_in, lw.w.f32, lw.b.f32, c_in)
-            assert _err(from_dev(h2), fh) <= TOL, ("fused h", B, t)
+            _check(from_dev(h2), fh, ("fused h", B, t))
             h, c = h2, c2
     # ragged H and B, c_out aliasing c_prev, closed form with zero recurrent weight
     rng = np.random.default_rng(77)
@@ -504,7 +606,8 @@ def test_lstm_from_precomputed_input_gates(rt, nb):
         hg, cg = rt.lstm_step_pre(f32_to_dev(pp), to_dev(hh), to_dev(ww), cdev, c_out=cdev)
         assert cg.data_ptr() == cdev.data_ptr()
         rh, rc = oracle.lstm_step_pre(pp, hh.f32, ww.f32, cc)
-        assert _err(from_dev(cg), rc) <= TOL and _err(from_dev(hg), rh) <= TOL, (B2, H2)
+        _check(from_dev(cg), rc, ("c", B2, H2), f32=True)
+        _check(from_dev(hg), rh, ("h", B2, H2))
     B2, H2 = 9, 16
     c0 = wl.uniform_bf16(rng, (B2, H2)).f32
     zero = torch.zeros((4 * H2, H2), dtype=torch.bfloat16, device="cuda")
@@ -544,20 +647,29 @@ def test_lstm_sequence_graph_with_projected_inputs(rt, nb):
 
 
 # ------------------------------------------------------------------ config 4
+# O against the oracle's unrounded chain: the GPU rounds P (the fused kernel: the un-normalised
+# exponentials) to bf16 before P.V, which adds to every element of O a sum of L independent rounding
+# errors of about 2^-9/sqrt(3) of the element's own scale; over 12 L 64 elements its largest value
+# reaches 5e-3 rms(O), so the absolute part of the element-wise bound is 2^-6 rms(O) here.
+P_ROUNDED_FLOOR = 2.0 ** -6
+
+
 def test_attention_chain(rt, nb):
     to_dev, _, from_dev, _ = _dev()
-    Ls = sorted(set([1, 2, 7, 8, 63, 64, 65, 129, 200, 512] + [int(v) for v in wl.config4_lengths()[:4]]))
+    # every L in 1..130 and 448..512: every residue of the 64- and 128-row tiles at both ends of the range
+    Ls = sorted(set(list(range(1, 131)) + list(range(448, 513)) + [200, 257, 300, 384] +
+                    [int(v) for v in wl.config4_lengths()[:8]]))
     for d, L in enumerate(Ls):
         q, k, v = wl.config4_qkv(d, L)
         s, p, o = rt.attention(to_dev(q), to_dev(k), to_dev(v))
         assert tuple(s.shape) == (12, L, L) and tuple(p.shape) == (12, L, L) and tuple(o.shape) == (12, L, 64)
         rs, rp, ro = oracle.attention(q.f32, k.f32, v.f32)
-        assert _err(from_dev(s), rs) <= TOL, ("S", L)
-        assert _err(from_dev(p), rp) <= TOL, ("P", L)
-        assert _err(from_dev(o), ro) <= TOL, ("O", L)
+        _check(from_dev(s), rs, ("S", L), f32=True)
+        _check(from_dev(p), rp, ("P", L))
+        _check(from_dev(o), ro, ("O", L), floor=P_ROUNDED_FLOOR)
         # teacher-forced second batch_matmul: the oracle applied to the GPU's own bf16 P
         ro2 = oracle.batch_matmul(from_dev(p), v.f32, False, 1.0)
-        assert _err(from_dev(o), ro2) <= TOL, ("O|P", L)
+        _check(from_dev(o), ro2, ("O|P", L))
         if L == 1:
             assert np.array_equal(from_dev(p), np.ones((12, 1, 1), np.float32))
             assert np.array_equal(from_dev(o), v.f32)
@@ -565,18 +677,21 @@ def test_attention_chain(rt, nb):
 
 def test_fused_attention_matches_the_oracle_chain(rt, nb):
     to_dev, _, from_dev, _ = _dev()
-    Ls = sorted(set([1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 300, 511, 512] +
+    Ls = sorted(set(list(range(1, 131)) + list(range(448, 513)) + [255, 256, 257, 300, 383, 384, 385] +
                     [int(v) for v in wl.config4_lengths()[:12]]))
     for d, L in enumerate(Ls):
         q, k, v = wl.config4_qkv(100 + d, L)
-        buf = torch.full((12, L + 1, 64), 768.0, dtype=torch.bfloat16, device="cuda")  # one guard row after the last head
-        o = rt.fused_attention(to_dev(q), to_dev(k), to_dev(v))
-        assert tuple(o.shape) == (12, L, 64)
+        # one guard row after the last head's last row: the kernel must stay inside o
+        buf = torch.full((12 * L + 1, 64), 768.0, dtype=torch.bfloat16, device="cuda")
+        o = rt.fused_attention(to_dev(q), to_dev(k), to_dev(v), out=buf[:12 * L].view(12, L, 64))
+        assert tuple(o.shape) == (12, L, 64) and o.data_ptr() == buf.data_ptr()
+        got = from_dev(buf)
+        assert np.all(got[12 * L:] == 768.0), ("wrote past the output", L)
         _, _, ro = oracle.attention(q.f32, k.f32, v.f32)
-        assert _err(from_dev(o), ro) <= TOL, ("O", L)
-        # and it agrees with the three-call chain on the GPU to rounding
-        _, _, o3 = rt.attention(to_dev(q), to_dev(k), to_dev(v))
-        assert _err(from_dev(o), from_dev(o3)) <= TOL, ("O vs chain", L)
+        _check(got[:12 * L].reshape(12, L, 64), ro, ("O", L), floor=P_ROUNDED_FLOOR)
+        if L % 16 in (0, 1, 15):   # and it agrees with the three-call chain on the GPU to rounding
+            _, _, o3 = rt.attention(to_dev(q), to_dev(k), to_dev(v))
+            assert _err(from_dev(o), from_dev(o3)) <= TOL, ("O vs chain", L)
     # closed forms: L = 1 returns V; Q = 0 returns the column mean of V
     q, k, v = wl.config4_qkv(7, 1)
     assert np.array_equal(from_dev(rt.fused_attention(to_dev(q), to_dev(k), to_dev(v))), v.f32)
@@ -599,7 +714,7 @@ def test_batch_matmul_general_shapes(rt, nb):
         for od in (nb.BF16, nb.F32):
             c = rt.batch_matmul(to_dev(a), to_dev(b), trans_b, 0.125, od)
             ref = oracle.batch_matmul(a.f32, b.f32, trans_b, 0.125)
-            assert _err(from_dev(c), ref) <= TOL, (T, M, N, K, trans_b, od)
+            _check(from_dev(c), ref, (T, M, N, K, trans_b, od), f32=od == nb.F32)
 
 
 def test_batch_matmul_nn_on_the_tiled_kernels_and_without_workspace(rt, nb):
@@ -617,8 +732,8 @@ def test_batch_matmul_nn_on_the_tiled_kernels_and_without_workspace(rt, nb):
         for od in (nb.BF16, nb.F32):
             tiled = rt.batch_matmul(to_dev(a), to_dev(b), False, 0.5, od)
             plain = rt.batch_matmul(to_dev(a), to_dev(b), False, 0.5, od, workspace=none)
-            assert _err(from_dev(tiled), ref) <= TOL, ("tiled", T, M, N, K, od)
-            assert _err(from_dev(plain), ref) <= TOL, ("plain", T, M, N, K, od)
+            _check(from_dev(tiled), ref, ("tiled", T, M, N, K, od), f32=od == nb.F32)
+            _check(from_dev(plain), ref, ("plain", T, M, N, K, od), f32=od == nb.F32)
     # K not a multiple of 8: no tiled plan, no workspace asked for
     p = nb.batch_matmul_plan(4, 33, 64, 33, False)
     assert p.name == "generic" and p.workspace_bytes == 0
@@ -634,7 +749,7 @@ def test_softmax_rows_on_gpu(rt, nb):
         s = (8 * (2 * rng.random((rows, cols)) - 1)).astype(np.float32)
         p = from_dev(rt.softmax_rows(f32_to_dev(s)))
         ref = oracle.softmax_rows(s)
-        assert _err(p, ref) <= TOL
+        _check(p, ref, ("softmax", rows, cols))
         assert np.max(np.abs(p.sum(-1) - 1)) < 2e-2  # bf16 rounding of each term
 
 
@@ -660,4 +775,91 @@ def test_errors_leave_outputs_untouched(rt, nb):
     y0 = rt.dense(xd[:0], wd, bd)
     assert tuple(y0.shape) == (0, 64)
     rt.dense(xd, wd, bd, out=y)
-    assert _err(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias")) <= TOL
+    _check(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias"), "after the refused calls")
+
+
+# ------------------------------------------------------------------ batch_matmul with one batch
+def test_batch_matmul_single_batch_large_and_small(rt, nb):
+    """batch = 1 takes dense-like plans: the launch must cover M on its own (no row split: rows past
+    the last full tile go through the masked copy), and the weight-streaming kernel must apply alpha."""
+    to_dev, _, from_dev, _ = _dev()
+    rng = np.random.default_rng(12)
+    # a shape the dense dispatch would split in two launches: guard rows behind the output stay untouched
+    M, N, K = 10764, 4096, 1024
+    p = nb.batch_matmul_plan(1, M, N, K, True)
+    assert p.split_rows == 0 and p.grid[0] == -(-M // p.bm) * -(-N // p.bn) and (p.residue_copy or M % p.bm == 0)
+    a, b = wl.uniform_bf16(rng, (1, M, K)), wl.normal_bf16(rng, (1, N, K))
+    buf = torch.full((M + 3, N), 768.0, dtype=torch.bfloat16, device="cuda")
+    rt.batch_matmul(to_dev(a), to_dev(b), True, 0.5, nb.BF16, out=buf[:M].view(1, M, N))
+    got = from_dev(buf)
+    assert np.all(got[M:] == 768.0)
+    rows = np.r_[0:4, M // 2:M // 2 + 4, M - 330:M]
+    ref = oracle.batch_matmul(a.f32[:, rows], b.f32, True, 0.5)
+    _check(got[rows], ref[0], ("bmm batch 1", M, N, K))
+    # few rows: the plan is the weight-streaming kernel, which must scale by alpha
+    for (M, N, K) in [(16, 128, 64), (64, 2304, 768), (5, 64, 128), (33, 512, 256)]:
+        assert nb.batch_matmul_plan(1, M, N, K, True).name == "skinny16", (M, N, K)
+        a, b = wl.uniform_bf16(rng, (1, M, K)), wl.uniform_bf16(rng, (1, N, K))
+        ref = oracle.batch_matmul(a.f32, b.f32, True, 0.125)
+        for od in (nb.BF16, nb.F32):
+            c = rt.batch_matmul(to_dev(a), to_dev(b), True, 0.125, od)
+            _check(from_dev(c), ref, ("bmm skinny", M, N, K, od), f32=od == nb.F32)
+
+
+# ------------------------------------------------------------------ tuned dispatch table
+def test_dense_through_a_tuned_table_entry(rt, nb):
+    """Section 3.5, tuning: an installed entry (3072 -> 768, M in 65..256: 64 x 128 tiles with K cut
+    in 4) decides the dispatch inside its range; the results across the range edges match the oracle
+    whichever side of an edge they fall on, and the built-in choice is back once the table is removed."""
+    N, K, epi = 768, 3072, nb.EPI_BIAS
+    builtin = {M: nb.dense_plan(M, N, K, epi) for M in (64, 65, 256, 257)}
+    try:
+        nb.dense_table_set(N, K, epi, [(65, 256, 3, 4)])
+        for M in (65, 100, 256):
+            p = nb.dense_plan(M, N, K, epi)
+            assert (p.name, p.split_k) == ("t64x128", 4)
+        assert nb.dense_plan(64, N, K, epi) == builtin[64] and nb.dense_plan(257, N, K, epi) == builtin[257]
+        _sweep(rt, nb, -1, N=N, K=K, Ms=[1, 63, 64, 65, 66, 100, 128, 129, 255, 256, 257, 258, 300], epilogue="bias")
+        # a tabled K split that does not fit the caller's scratch is skipped, not an error
+        to_dev, _, from_dev, _ = _dev()
+        rng = np.random.default_rng(78)
+        x, w, b = wl.uniform_bf16(rng, (100, K)), wl.normal_bf16(rng, (N, K)), wl.uniform_bf16(rng, (N,))
+        none = torch.empty(0, dtype=torch.uint8, device="cuda")
+        y = rt.dense(to_dev(x), to_dev(w), to_dev(b), epi, workspace=none)
+        _check(from_dev(y), oracle.dense(x.f32, w.f32, b.f32, "bias"), "tabled split without scratch")
+    finally:
+        nb.dense_table_set(N, K, epi, [])
+    for M, p in builtin.items():
+        assert nb.dense_plan(M, N, K, epi) == p
+
+
+def test_runtime_refuses_tensors_it_cannot_pass_as_plain_pointers(rt, nb):
+    """The C ABI takes contiguous bf16 device memory: a strided view, another dtype or a host tensor
+    must be refused by the caller-side wrapper, not read as packed bf16."""
+    x = torch.zeros((8, 128), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((64, 128), dtype=torch.bfloat16, device="cuda")
+    b = torch.zeros((64,), dtype=torch.bfloat16, device="cuda")
+    wide = torch.zeros((8, 256), dtype=torch.bfloat16, device="cuda")
+    for bad_x, bad_w, bad_b in [(wide[:, :128], w, b), (x.float(), w, b), (x, w.float(), b), (x.cpu(), w, b),
+                                (x, w, b.float()), (x, w.t().contiguous().t(), b)]:
+        with pytest.raises(nb.NimbleError):
+            rt.dense(bad_x, bad_w, bad_b)
+    with pytest.raises(nb.NimbleError):
+        rt.dense(x, w, b, out=torch.zeros((8, 128), dtype=torch.bfloat16, device="cuda")[:, :64])
+    with pytest.raises(nb.NimbleError):
+        rt.dense(x, w, b, out=torch.zeros((8, 64), dtype=torch.float32, device="cuda"))
+    q = torch.zeros((2, 8, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(nb.NimbleError):
+        rt.batch_matmul(q.transpose(1, 2), q, True)
+    with pytest.raises(nb.NimbleError):
+        rt.fused_attention(q, q.float(), q)
+    h = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+    wl_ = torch.zeros((256, 192), dtype=torch.bfloat16, device="cuda")
+    bl = torch.zeros((256,), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(nb.NimbleError):
+        rt.lstm_step(x, h, wl_, bl, c.bfloat16())
+    with pytest.raises(nb.NimbleError):
+        rt.lstm_step(x, h.float(), wl_, bl, c)
+    rt.lstm_step(x, h, wl_, bl, c)      # the well-formed call goes through
+    torch.cuda.synchronize()

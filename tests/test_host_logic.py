@@ -241,14 +241,14 @@ def test_lstm_plan():
 def test_device_entry_points_validate_before_touching_the_gpu():
     # every one of these must be refused on the host (no GPU in this process)
     lib = nb.load()
-    assert lib.nimble_dense_dyn(None, None, None, None, 4, 128, 128, 1, 0, -1, None, 0, None) == -1
-    assert lib.nimble_dense_dyn(16, 32, 48, 64, -4, 128, 128, 1, 0, -1, None, 0, None) == -8
-    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 7, 0, -1, None, 0, None) == -8
-    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 1, 5, -1, None, 0, None) == -4
-    assert lib.nimble_dense_dyn(16, 32, 48, 68, 4, 128, 128, 1, 0, -1, None, 0, None) == -5
-    assert lib.nimble_dense_dyn(16, 32, None, 64, 4, 128, 128, 1, 0, -1, None, 0, None) == -1
+    assert lib.nimble_dense_dyn(None, None, None, None, 4, 128, 128, 1, 0, None, 0, None) == -1
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, -4, 128, 128, 1, 0, None, 0, None) == -8
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 7, 0, None, 0, None) == -8
+    assert lib.nimble_dense_dyn(16, 32, 48, 64, 4, 128, 128, 1, 5, None, 0, None) == -4
+    assert lib.nimble_dense_dyn(16, 32, 48, 68, 4, 128, 128, 1, 0, None, 0, None) == -5
+    assert lib.nimble_dense_dyn(16, 32, None, 64, 4, 128, 128, 1, 0, None, 0, None) == -1
     # M = 0 is a legal instantiation of the dynamic dimension: nothing to do
-    assert lib.nimble_dense_dyn(None, None, None, None, 0, 128, 128, 1, 0, -1, None, 0, None) == 0
+    assert lib.nimble_dense_dyn(None, None, None, None, 0, 128, 128, 1, 0, None, 0, None) == 0
     assert lib.nimble_batch_matmul_dyn(None, None, None, 12, 0, 0, 64, 1, 0.125, 1, None, 0, None) == 0
     assert lib.nimble_batch_matmul_dyn(16, 32, 50, 12, 4, 4, 64, 1, 0.125, 1, None, 0, None) == -5
     assert lib.nimble_softmax_rows_dyn(None, None, 0, 5, None) == 0
@@ -321,6 +321,13 @@ def test_plan_invariants_on_random_shapes():
         assert p.grid[0] == -(-rows // p.bm) * -(-N // p.bn)
         if p.split_rows:
             assert p.split_rows % p.bm == 0 and 0 < p.split_rows < M and p.split_k == 1
+            # the second launch is reported as it will run: planned alone it gives the same variant, K
+            # split and scratch need
+            tail = nb.dense_plan(M - p.split_rows, N, K, epi)
+            assert (p.residue_variant, p.residue_split_k) == (tail.variant, tail.split_k)
+            if tail.split_rows == 0:
+                assert p.workspace_bytes == tail.workspace_bytes
+            continue
         if p.split_k > 1:
             assert N % p.bn == 0 and K % 32 == 0 and p.workspace_bytes == p.split_k * M * N * 4
             assert p.workspace_bytes <= 64 << 20   # plans are made within the default scratch
@@ -342,3 +349,124 @@ def test_batch_matmul_plan_nn_workspace():
         p = nb.batch_matmul_plan(T, M, N, K, False)
         assert p.name == "generic" and p.workspace_bytes == 0
     assert nb.batch_matmul_plan(12, 512, 512, 64, True).workspace_bytes == 0
+
+
+def test_batch_matmul_plans_are_one_launch_covering_every_row():
+    """batch_matmul launches its plan as it stands: the plan must never split the rows in two
+    launches or cut K, and the r = 0 copy (no bounds code) may only be chosen when no tile is ragged."""
+    rng = np.random.default_rng(11)
+    shapes = [(1, 10764, 4096, 1024), (1, 8300, 1024, 4096), (1, 16, 128, 128), (1, 64, 2304, 768)]
+    for _ in range(1500):
+        T = int(rng.choice([1, 1, 2, 12, 40]))
+        M = int(rng.choice([rng.integers(1, 70), rng.integers(65, 3000), rng.integers(3000, 40000)]))
+        N = int(rng.choice([rng.integers(1, 600), rng.integers(1, 40) * 128, rng.integers(1, 17) * 256]))
+        K = int(rng.choice([rng.integers(1, 600), rng.integers(1, 130) * 32, rng.integers(1, 65) * 64]))
+        shapes.append((T, M, N, K))
+    for (T, M, N, K) in shapes:
+        for trans_b in (True, False):
+            p = nb.batch_matmul_plan(T, M, N, K, trans_b)
+            assert p.split_rows == 0, (T, M, N, K, trans_b, p)
+            assert p.grid[2] == (T if p.name != "skinny16" else 1)
+            if p.variant >= 2:
+                assert p.split_k == 1
+                assert p.grid[0] == -(-M // p.bm) * -(-N // p.bn)
+                if not p.residue_copy:
+                    assert M % p.bm == 0 and N % p.bn == 0 and K % p.bk == 0, (T, M, N, K, p)
+            if p.name == "skinny16":
+                assert T == 1 and trans_b and M <= 64
+
+
+def test_lstm_pre_shape_matches_oracle():
+    for B in (0, 1, 16, 33, 64):
+        args = ((B, 2048), (B, 512), (B, 512), (2048, 512))
+        assert nb.lstm_pre_shape(*args) == oracle.lstm_pre_shape(*args) == ((B, 512), (B, 512))
+    for bad in [((3, 2048), (4, 512), (3, 512), (2048, 512)), ((3, 2047), (3, 512), (3, 512), (2048, 512)),
+                ((3, 2048), (3, 512), (3, 511), (2048, 512)), ((3, 2048), (3, 512), (3, 512), (2048, 1024)),
+                ((3, 2048), (3, 512), (3, 512), (2040, 512)), ((2, 2048), (3, 512), (3, 512), (2048, 512))]:
+        with pytest.raises(nb.NimbleError) as e:
+            nb.lstm_pre_shape(*bad)
+        assert e.value.code == -3
+        with pytest.raises(oracle.OracleShapeError):
+            oracle.lstm_pre_shape(*bad)
+    with pytest.raises(nb.NimbleError) as e:
+        nb.lstm_pre_shape((3, 2048), (3, -512), (3, 512), (2048, 512))
+    assert e.value.code == -8
+    lib = nb.load()
+    out = (ctypes.c_int64 * 2)(-5, -6)
+    four = [(ctypes.c_int64 * 2)(*v) for v in ((3, 32), (3, 8), (3, 8), (32, 9))]
+    assert lib.nimble_lstm_pre_shape(*four, out, out) == -3 and (out[0], out[1]) == (-5, -6)  # untouched on error
+    assert lib.nimble_lstm_pre_shape(None, four[1], four[2], four[3], out, out) == -1
+
+
+def test_tuned_table_overrides_the_cost_model():
+    """Section 3.5, tuning: an installed entry decides the dispatch inside its M range and nowhere
+    else; entries that cannot run are skipped; count = 0 removes the table."""
+    N, K, epi = 768, 3072, nb.EPI_BIAS
+    before = {M: nb.dense_plan(M, N, K, epi) for M in (1, 64, 65, 100, 256, 257, 300, 1000)}
+    others = [(100, N, K, nb.EPI_NONE), (100, N, K, nb.EPI_BIAS_GELU_ERF), (100, 2304, 768, epi), (100, K, N, epi)]
+    before_others = [nb.dense_plan(*o) for o in others]
+    try:
+        # (m_lo, m_hi, variant, split_k): 64x128 tiles with K cut in 4 for 65..256, weight streaming up to 64
+        nb.dense_table_set(N, K, epi, [(65, 256, 3, 4), (1, 64, 1, 1)])
+        for M in (65, 100, 256):
+            p = nb.dense_plan(M, N, K, epi)
+            assert (p.name, p.split_k, p.split_rows) == ("t64x128", 4, 0)
+            assert p.workspace_bytes == 4 * M * N * 4 and p.grid[:2] == (-(-M // 64) * 6, 4)
+        for M in (1, 64):
+            assert nb.dense_plan(M, N, K, epi).name == "skinny16"
+        for M in (257, 300, 1000):          # outside every range: the cost model, unchanged
+            assert nb.dense_plan(M, N, K, epi) == before[M]
+        # keyed by (N, K, epilogue): other layers and other epilogues are not affected
+        assert [nb.dense_plan(*o) for o in others] == before_others
+        # a forced variant ignores the table
+        assert nb.dense_plan(100, N, K, epi, force_variant=4).name == "t128x128"
+        # an entry that cannot run this shape is skipped: K = 3072 + 8 has no whole 32-wide stages to cut
+        nb.dense_table_set(N, K + 8, epi, [(1, 4096, 4, 4)])
+        p = nb.dense_plan(300, N, K + 8, epi)
+        assert not (p.name == "t128x128" and p.split_k == 4)
+        nb.dense_table_set(N, K + 8, epi, [])
+        # replacing a table replaces every entry of that key
+        nb.dense_table_set(N, K, epi, [(100, 100, 5, 1)])
+        assert nb.dense_plan(100, N, K, epi).name == "t256x128"
+        assert nb.dense_plan(65, N, K, epi) == before[65]
+        nb.dense_table_set(N, K, epi, [])
+        for M, p in before.items():
+            assert nb.dense_plan(M, N, K, epi) == p
+        # malformed entries are refused and leave no table behind
+        for bad in [[(5, 4, 3, 1)], [(-1, 4, 3, 1)], [(1, 4, 0, 1)], [(1, 4, 7, 1)], [(1, 65, 1, 1)], [(1, 4, 3, 65)]]:
+            with pytest.raises(nb.NimbleError) as e:
+                nb.dense_table_set(N, K, epi, bad)
+            assert e.value.code == -8
+            assert nb.dense_plan(4, N, K, epi).name == "skinny16"
+        assert nb.dense_plan(100, N, K, epi) == before[100]
+    finally:
+        nb.dense_table_set(N, K, epi, [])
+        nb.dense_table_set(N, K + 8, epi, [])
+
+
+def test_tabled_k_split_needs_the_workspace_it_asks_for():
+    """The entry point plans within the scratch the caller brings: a tabled K split that does not fit
+    is skipped there (checked here through the plan a caller with no scratch would get: the device
+    entry point refuses on the host when pointers are null, after planning)."""
+    N, K, epi = 768, 3072, nb.EPI_BIAS
+    lib = nb.load()
+    try:
+        nb.dense_table_set(N, K, epi, [(65, 256, 3, 4)])
+        # with no workspace the tabled split cannot run; the call still plans (and then stops at the
+        # null tensors): no NIMBLE_ERR_WORKSPACE
+        assert lib.nimble_dense_dyn(None, None, None, None, 100, N, K, epi, 0, None, 0, None) == -1
+    finally:
+        nb.dense_table_set(N, K, epi, [])
+
+
+def test_forced_variant_and_k_split_from_the_environment():
+    """NIMBLE_FORCE_VARIANT (a measurement knob, read once per process) carries the forced K split in
+    bits 8..15 like the force_variant argument does."""
+    import subprocess
+    import sys
+    code = ("import paper_2006_03031_amd as nb; p = nb.dense_plan(300, 768, 3072); "
+            "print(p.name, p.split_k, p.workspace_bytes)")
+    env = dict(os.environ, NIMBLE_FORCE_VARIANT=str(4 | (2 << 8)))
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], env=env, cwd=root, capture_output=True, text=True, check=True)
+    assert out.stdout.split() == ["t128x128", "2", str(2 * 300 * 768 * 4)]

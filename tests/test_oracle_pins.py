@@ -516,3 +516,91 @@ def test_workload_draws_are_seeded_and_in_range():
     assert len(L) == 100 and L.min() >= 1 and L.max() <= 512
     w = wl.config2_weights()
     assert w.w.shape == (2048, 1024) and abs(float(w.w.f32.std()) - 0.02) < 1e-3
+
+
+# ------------------------------------------------------------------ the yardsticks themselves
+def test_normwise_rel_error_known_answers():
+    """||got - ref||_F / ||ref||_F on hand-computed cases (3-4-5 triangles): a metric that
+    returned too small a value would let every parity test pass."""
+    e = oracle.normwise_rel_error
+    assert e([3.0, 4.0], [3.0, 4.0]) == 0.0
+    assert e([0.0, 0.0], [3.0, 4.0]) == 1.0                     # ||ref|| / ||ref||
+    assert e([3.0, 4.0], [0.0, 0.0]) == float("inf")            # zero reference, non-zero output
+    assert e([0.0, 0.0], [0.0, 0.0]) == 0.0
+    assert e([6.0, 8.0], [3.0, 4.0]) == 1.0                     # got = 2 ref: ||ref|| / ||ref||
+    assert e([3.0, 0.0], [0.0, 4.0]) == 1.25                    # ||(3,-4)|| / 4 = 5/4
+    eps = 2.0 ** -10
+    assert e([1.0, eps, 0.0, 0.0], [1.0, 0.0, 0.0, 0.0]) == eps
+    # relative: scaling both by 1000 (or by 2^-40) changes nothing; it is not symmetric in its arguments
+    assert e([3000.0, 0.0], [0.0, 4000.0]) == 1.25
+    assert e(np.ldexp([3.0, 0.0], -40), np.ldexp([0.0, 4.0], -40)) == 1.25
+    assert e([0.0, 4.0], [3.0, 0.0]) == 5.0 / 3.0
+    # the Frobenius norm runs over every element of a matrix, whatever its shape, in float64
+    got = np.zeros((4, 6), np.float32)
+    ref = np.zeros((4, 6), np.float32)
+    ref[1, 2], ref[3, 5] = 3.0, 4.0
+    got[1, 2], got[3, 5], got[0, 0] = 3.0, 4.0, 12.0            # one wrong element of size 12: 12/5
+    assert e(got, ref) == 2.4
+    assert e(got.reshape(2, 12), ref.reshape(2, 12)) == 2.4
+    # one element off by d among n equal ones: d / sqrt(n)
+    ref = np.ones(10000)
+    got = ref.copy()
+    got[1234] += 0.5
+    assert abs(e(got, ref) - 0.005) < 1e-15
+
+
+def test_maxnorm_rel_error_known_answers():
+    m = oracle.maxnorm_rel_error
+    assert m([3.0, 4.0], [3.0, 4.0]) == 0.0
+    assert m([0.0, 0.0], [3.0, 4.0]) == 1.0                     # max|d| = 4, max|ref| = 4
+    assert m([3.0, 5.0], [3.0, 4.0]) == 0.25
+    assert m([4.0, 4.0], [3.0, -4.0]) == 2.0                    # the sign matters: |4 - (-4)| / 4
+    assert m([1.0], [0.0]) == float("inf") and m([0.0], [0.0]) == 0.0 and m([], []) == 0.0
+    assert m([3000.0, 5000.0], [3000.0, 4000.0]) == 0.25        # relative
+    # a single wrong element sets it, however many right ones surround it
+    ref = np.ones((100, 100))
+    got = ref.copy()
+    got[7, 9] = 1.5
+    assert m(got, ref) == 0.5
+
+
+def test_elementwise_excess_known_answers():
+    x = oracle.elementwise_excess
+    ref = np.array([3.0, -4.0, 0.0, 5.0])                        # rms = sqrt(50 / 4)
+    rms = np.sqrt(12.5)
+    assert x(ref, ref, 0.01, 0.01) == 0.0
+    got = ref + np.array([0.0, 0.0, 0.5, 0.0])                   # an element whose reference is 0: only the floor allows it
+    assert abs(x(got, ref, 0.01, 0.01) - 0.5 / (0.01 * rms)) < 1e-12
+    got = ref + np.array([0.0, 0.08, 0.0, 0.0])                  # |d| = 0.08 at |ref| = 4
+    assert abs(x(got, ref, 0.01, 0.0) - 2.0) < 1e-12             # twice the allowed 1 %
+    assert abs(x(got, ref, 0.02, 0.0) - 1.0) < 1e-12             # exactly at the bound
+    assert abs(x(got, ref, 0.0, 0.01) - 0.08 / (0.01 * rms)) < 1e-12
+    # the maximum over elements, not a mean: one bad element among a million good ones shows fully
+    ref = np.ones(1_000_000)
+    got = ref.copy()
+    got[123456] = 1.5
+    assert abs(x(got, ref, 0.25, 0.25) - 1.0) < 1e-12
+    assert oracle.normwise_rel_error(got, ref) == 0.0005        # where the norm alone would have passed 5e-3
+    assert x([0.0, 1e-30], [0.0, 0.0], 0.5, 0.5) == float("inf") and x([0.0], [0.0], 0.5, 0.5) == 0.0
+    assert x(2 * ref, 2 * got, 0.25, 0.25) > 0                  # arguments are (got, ref), both scale together
+    assert abs(x(1000 * got, 1000 * ref, 0.25, 0.25) - 1.0) < 1e-9
+
+
+def test_lstm_pre_shape_function():
+    """The cell with a precomputed input share is the fused cell with no input columns: its shape
+    function accepts exactly what the fused one accepts for x of width 0, with pre = (B, 4H)."""
+    for B in (0, 1, 16, 33):
+        for H in (8, 24, 512):
+            assert oracle.lstm_pre_shape((B, 4 * H), (B, H), (B, H), (4 * H, H)) == ((B, H), (B, H))
+            assert oracle.lstm_shape((B, 0), (B, H), (B, H), (4 * H, H)) == ((B, H), (B, H))
+            for bad_h, bad_c, bad_w in [((B + 1, H), (B, H), (4 * H, H)), ((B, H), (B, H + 8), (4 * H, H)),
+                                        ((B, H), (B, H), (4 * H + 1, H)), ((B, H), (B, H), (4 * H, H + 1))]:
+                with pytest.raises(oracle.OracleShapeError):
+                    oracle.lstm_pre_shape((B, 4 * H), bad_h, bad_c, bad_w)
+                with pytest.raises(oracle.OracleShapeError):
+                    oracle.lstm_shape((B, 0), bad_h, bad_c, bad_w)
+            for bad_pre in [(B + 1, 4 * H), (B, 4 * H - 1), (B, H)]:
+                with pytest.raises(oracle.OracleShapeError):
+                    oracle.lstm_pre_shape(bad_pre, (B, H), (B, H), (4 * H, H))
+    with pytest.raises(oracle.OracleShapeError):
+        oracle.lstm_pre_shape((3, 32, 1), (3, 8), (3, 8), (32, 8))
