@@ -200,6 +200,21 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
                      int64_t K, int epilogue, int out_dtype, void* workspace, size_t workspace_bytes,
                      void* stream);
 
+/* nimble_dense_dyn for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same operation, same
+ * dispatch, same kernels and the same result bit for bit as nimble_dense_dyn called with the
+ * workspace its plan asks for; the K-split partial sums go to a scratch array built into the
+ * library (NIMBLE_NOALLOC_SCRATCH_BYTES of device memory per GPU, held from the time the
+ * library's code is loaded on that GPU until the process ends).  The call allocates and frees
+ * nothing.  A shape whose plan (nimble_dense_plan) needs more scratch than that is refused with
+ * NIMBLE_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share that GPU's scratch:
+ * calls that may overlap (different streams, different host threads) race on it and must use
+ * nimble_dense_dyn with workspaces of their own instead; calls on one stream are ordered and safe.
+ * Nothing in the scratch carries over between calls. */
+#define NIMBLE_NOALLOC_SCRATCH_BYTES (32u << 20)
+int nimble_dense_noalloc_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,
+                             int64_t N, int64_t K, int epilogue, int out_dtype, void* stream);
+
 /* batch_matmul with dynamic M (and N or K when they are the same symbol):
  *   trans_b != 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,n,k]
  *   trans_b == 0: c[t,m,n] = alpha * sum_k a[t,m,k] * b[t,k,n]

@@ -101,6 +101,7 @@ def load():
     lib.nimble_last_error.restype = ctypes.c_char_p
     lib.nimble_lstm_pre_shape.argtypes = [ip, ip, ip, ip, ip, ip]
     lib.nimble_dense_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.nimble_dense_noalloc_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, vp]
     lib.nimble_dense_variant_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
     lib.nimble_batch_matmul_dyn.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_float, i32, vp,
                                             ctypes.c_size_t, vp]
@@ -268,6 +269,15 @@ def lstm_plan(B: int, Ix: int, H: int) -> Plan:
 def nimble_dense_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,
                      out_dtype: int = BF16, workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
     _check(load().nimble_dense_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, workspace, workspace_bytes, stream))
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def nimble_dense_noalloc_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,
+                             out_dtype: int = BF16, stream: int = 0) -> None:
+    """nimble_dense_dyn on the library's built-in scratch: allocates nothing, takes no workspace."""
+    _check(load().nimble_dense_noalloc_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, stream))
 
 
 def nimble_dense_variant_dyn(x: int, w: int, bias: int, y: int, M: int, N: int, K: int, epilogue: int,

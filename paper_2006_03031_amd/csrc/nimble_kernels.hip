@@ -25,6 +25,7 @@
 
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 
 #include "device_common.h"
 #include "gemm_ring_kernel.h"
@@ -155,6 +156,38 @@ static int launch_gemm(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
 
 static inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Built-in scratch of nimble_dense_noalloc_dyn: the f32 partial sums of a K split live here instead
+// of in memory the caller brings.  Every GPU the library runs on holds its own copy of the array
+// (at its own address) from the moment the code object is loaded there until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress, never a device address:
+// kernels are given the pointer that call returns.
+static __device__ __align__(256) unsigned char scratch[NIMBLE_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // per device, looked up once with that device current
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`, or null after fail().
+static void* scratch_of_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(NIMBLE_ERR_HIP, "hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fail(NIMBLE_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace nimble
 
 using namespace nimble;
@@ -185,6 +218,34 @@ int nimble_dense_dyn(const void* x, const void* w, const void* bias, void* y, in
                      void* stream) {
   return nimble_dense_variant_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, NIMBLE_VAR_AUTO, workspace,
                                   workspace_bytes, stream);
+}
+
+int nimble_dense_noalloc_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M, int64_t N,
+                             int64_t K, int epilogue, int out_dtype, void* stream) {
+  clear_error();
+  if (epilogue < NIMBLE_EPI_NONE || epilogue > NIMBLE_EPI_BIAS_GELU_ERF)
+    return fail(NIMBLE_ERR_ARG, "unknown epilogue %d", epilogue);
+  if (out_dtype != NIMBLE_BF16 && out_dtype != NIMBLE_F32) return fail(NIMBLE_ERR_DTYPE, "unknown dtype %d", out_dtype);
+  // the plan a caller would get who brings whatever scratch the dispatch function asks for: if it
+  // fits the built-in scratch, planning within the built-in scratch gives the same plan
+  PlanOptions opt;
+  opt.max_workspace = ~0ull;
+  nimble_plan p;
+  int rc = plan_dense(1, M, N, K, epilogue, NIMBLE_VAR_AUTO, opt, &p);
+  if (rc != NIMBLE_OK) return rc;
+  if (p.workspace_bytes > (uint64_t)NIMBLE_NOALLOC_SCRATCH_BYTES)
+    return fail(NIMBLE_ERR_WORKSPACE,
+                "dense %lld x %lld x %lld needs %llu bytes of scratch, the built-in scratch holds %llu: "
+                "use nimble_dense_dyn with a workspace",
+                (long long)M, (long long)N, (long long)K, (unsigned long long)p.workspace_bytes,
+                (unsigned long long)NIMBLE_NOALLOC_SCRATCH_BYTES);
+  if (M == 0 || N == 0) return NIMBLE_OK;
+  void* ws = scratch_of_current_device();
+  if (!ws) return NIMBLE_ERR_HIP;
+  // nothing in the scratch needs clearing: every slice of a K split writes its whole plane of
+  // partial sums before the reduction kernel reads it
+  return nimble_dense_variant_dyn(x, w, bias, y, M, N, K, epilogue, out_dtype, NIMBLE_VAR_AUTO, ws,
+                                  (size_t)NIMBLE_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int nimble_dense_variant_dyn(const void* x, const void* w, const void* bias, void* y, int64_t M,

@@ -470,3 +470,16 @@ def test_forced_variant_and_k_split_from_the_environment():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     out = subprocess.run([sys.executable, "-c", code], env=env, cwd=root, capture_output=True, text=True, check=True)
     assert out.stdout.split() == ["t128x128", "2", str(2 * 300 * 768 * 4)]
+
+
+def test_no_alloc_entry_point_refuses_what_its_scratch_cannot_hold():
+    # host-side validation only (no GPU in this process): the refusal comes before any device access
+    lib = nb.load()
+    big = nb.dense_plan(1088, 4096, 16384, nb.EPI_BIAS)
+    assert big.workspace_bytes > nb.NOALLOC_SCRATCH_BYTES
+    assert lib.nimble_dense_noalloc_dyn(16, 32, 48, 64, 1088, 4096, 16384, 1, 0, None) == -6
+    assert "scratch" in nb.last_error()
+    assert lib.nimble_dense_noalloc_dyn(16, 32, 48, 64, 4, 128, 128, 7, 0, None) == -8      # unknown epilogue
+    assert lib.nimble_dense_noalloc_dyn(16, 32, 48, 64, 4, 128, 128, 1, 9, None) == -4      # unknown dtype
+    assert lib.nimble_dense_noalloc_dyn(16, 32, 48, 64, -4, 128, 128, 1, 0, None) == -8
+    assert lib.nimble_dense_noalloc_dyn(None, None, None, None, 0, 128, 128, 1, 0, None) == 0  # M = 0: nothing to do
