@@ -153,12 +153,24 @@ static double tiled_cost_us(int v, int64_t batch, int64_t rows, int64_t N, int64
 // the same for every single-launch choice) and the weight-streaming estimate includes.
 static const double kLaunchUs = 3.5;
 
+// Whether a weight-streaming launch of 16-row blocks runs the LDS-staged streaming kernel (the
+// launcher applies the same test): K in whole 64-wide stages, 32-bit byte offsets into the weights.
+// NIMBLE_NO_STREAM (a measurement knob) turns that kernel off in both places.
+bool stream_kernel_shape_ok(int64_t N, int64_t K) {
+  static const bool off = std::getenv("NIMBLE_NO_STREAM") != nullptr;
+  return !off && K >= 64 && K % 64 == 0 && (uint64_t)N * (uint64_t)K * 2u < (1ull << 32);
+}
+
 // Row blocks of a weight-streaming launch: a workgroup takes 16 weight rows and 16..64
-// activation rows.  A narrow layer (few weight rows) fills the chip only when the activation
-// rows are spread over several workgroups, each re-reading its weight rows (they meet in L2);
-// a wide layer already has a workgroup per compute unit and keeps one block per 64 rows so that
-// the weights cross HBM once.
-static int64_t skinny_row_blocks(int64_t rows, int64_t N) {
+// activation rows.  Where the streaming kernel runs and the layer stays in the caches, every
+// workgroup takes 16 activation rows (each block re-reads the weights, which then come from L2:
+// the BERT-base and LSTM layers at 17..64 rows run 5-25 % faster that way than in blocks of 32..64
+// rows on the register-layout kernel).  Otherwise: a narrow layer (few weight rows) fills the chip
+// only when the activation rows are spread over several workgroups, each re-reading its weight
+// rows (they meet in L2); a wide layer already has a workgroup per compute unit and keeps one block
+// per 64 rows so that the weights cross HBM once.
+static int64_t skinny_row_blocks(int64_t rows, int64_t N, int64_t K, bool stream_ok) {
+  if (stream_ok && (double)N * (double)K * 2.0 <= kCachedWeightBytes) return rows > 16 ? ceil_div(rows, 16) : 1;
   int64_t blocks = kCUs / ceil_div(N, 16);
   const int64_t most = ceil_div(rows, 16), fewest = ceil_div(rows, 64);
   if (blocks > most) blocks = most;
@@ -166,16 +178,31 @@ static int64_t skinny_row_blocks(int64_t rows, int64_t N) {
   return blocks < 1 ? 1 : blocks;
 }
 
-// The weight-streaming kernel: launch latency, then whichever is longer of streaming W (the
-// activations are re-read once per 16 weight rows, which shows from 32 rows on) and one
-// workgroup's own walk over K (N / 16 workgroups only: a short, wide layer leaves most of the
-// chip idle).  Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
+// The weight-streaming kernels, launch latency included.
+// Streaming kernel (blocks of 16 rows): whichever is longer of the weight stream and one wave's
+// walk over its K stages, per round of workgroups.  Measured: a 134 MB layer from HBM 24.0 us at
+// 1..8 rows and 27.9 at 16; cache-resident layers 2.5-2.8 us at K = 768..1024, 3.3-4.1 at K =
+// 3072..4096 (0.14-0.20 us per stage of a wave's eight-way share of K); 17..64 rows on the 8 MB
+// layers 4.2-7.2 us.
+// Register-layout kernel (any K): the activations are re-read once per 16 weight rows, which shows
+// from 32 rows on; N / 16 workgroups only, so a short, wide layer leaves most of the chip idle.
+// Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
 static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
-  const int64_t nblocks = skinny_row_blocks(rows, N);
+  const double bytes = (double)N * (double)K * 2.0;
+  const bool cached = bytes <= kCachedWeightBytes;
+  if (stream_kernel_shape_ok(N, K) && (rows <= 16 || cached)) {
+    const int64_t blocks16 = ceil_div(rows, 16);
+    const int64_t rounds = ceil_div(ceil_div(N, 16) * blocks16, kCUs);
+    const double rate = cached ? 22e6 : (rows <= 8 ? 6.2e6 : 5.26e6);  // bytes per microsecond
+    const double stream = bytes * (cached ? 1.0 : (double)blocks16) / rate;
+    const double walk = (double)ceil_div(ceil_div(K, 64), 8) * (rows <= 8 ? 0.14 : 0.20) * (double)rounds +
+                        0.35 * (double)(rounds - 1);
+    return kLaunchUs + (stream > walk ? stream : walk);
+  }
+  const int64_t nblocks = skinny_row_blocks(rows, N, K, false);
   const double mt = (double)ceil_div(rows, 16 * nblocks);
   const double blocks = (double)ceil_div(rows, 64);
-  const double bytes = (double)N * (double)K * 2.0;
-  const double rate = bytes > kCachedWeightBytes ? 5.94e6 : 6.79e6;  // bytes per microsecond
+  const double rate = !cached ? 5.94e6 : 6.79e6;  // bytes per microsecond
   const double stream = bytes / rate * (1.0 + 0.553 * (double)rows / (double)nblocks / 16.0);
   const double walk = (double)ceil_div(K, 128) * mt * 0.126;
   return kLaunchUs + blocks * (stream > walk ? stream : walk);
@@ -245,8 +272,10 @@ static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int
         }
       }
   }
-  // up to 64 rows the small tiles (with K cut) compete with weight streaming (compared launch included)
-  if (skinny_us >= 0.0 && (best.variant < 0 || skinny_us <= best.us + kLaunchUs)) {
+  // up to 64 rows the small tiles (with K cut) compete with weight streaming (compared launch included);
+  // up to 16 rows the streaming kernel was the fastest choice on every layer measured
+  if (skinny_us >= 0.0 && (best.variant < 0 || skinny_us <= best.us + kLaunchUs ||
+                           (rows <= 16 && stream_kernel_shape_ok(N, K)))) {
     best = Launch();
     best.variant = NIMBLE_VAR_SKINNY16;
     best.us = skinny_us;
@@ -387,7 +416,7 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     p->residue_copy = (p->r != 0 || N % v.bn != 0 || K % v.bk != 0) ? 1 : 0;
     p->split_k = 4;  // the four waves of a workgroup each take a quarter of K
     p->grid[0] = (uint32_t)ceil_div(N, v.bn);
-    p->grid[1] = (uint32_t)skinny_row_blocks(M, N);  // up to four 16-row tiles per workgroup
+    p->grid[1] = (uint32_t)skinny_row_blocks(M, N, K, stream_kernel_shape_ok(N, K));  // up to four 16-row tiles per workgroup
     p->grid[2] = 1;
     p->block = 256;
     return NIMBLE_OK;
@@ -631,7 +660,7 @@ int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {
   plan->grid[0] = (uint32_t)ceil_div(H, 4);
   // row blocks as for the weight-streaming dense (4H weight rows; measured at H = 512: 2 blocks
   // of 32 rows at B = 64 take 5.6 us against 7.9 us for one block of 64)
-  plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H);
+  plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H, Ix + H, stream_kernel_shape_ok(4 * H, Ix + H) && Ix % 64 == 0);
   plan->grid[2] = 1;
   plan->block = 256;
   return NIMBLE_OK;

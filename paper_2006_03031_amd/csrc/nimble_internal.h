@@ -25,6 +25,10 @@ bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
 // bm = 0 or the variant's own height: always; else the heights the variant is also built at.
 bool tile_rows_ok(int variant, int bm, int64_t N, int64_t K);
 
+// Whether a weight-streaming launch of 16-row blocks over an [N, K] weight can run the LDS-staged
+// streaming kernel (the LSTM cell needs Ix % 64 == 0 besides).
+bool stream_kernel_shape_ok(int64_t N, int64_t K);
+
 struct PlanOptions {
   uint64_t max_workspace = 0;   // bytes of caller scratch available (split-K partial sums)
   bool allow_row_split = true;  // may dispatch x = bm*k + r as two launches

@@ -17,6 +17,10 @@
 //       streamed from HBM exactly once straight into MFMA operands, the four waves of a
 //       workgroup split K and reduce through LDS.  LSTM=true gathers the four gate rows of
 //       four hidden units and applies the cell update in the epilogue.
+//   stream_kernel.h      stream_kernel<LSTM,S,NW,XR>: the weight-streaming kernel for up to 16 rows per
+//       workgroup and K in whole 64-wide stages: operands staged through per-wave LDS rings by
+//       direct global->LDS loads of whole 128-byte lines (what bounds skinny_kernel is cache-line
+//       look-ups, 64 per KiB with its register-layout loads).
 //   misc_kernels.h       generic_kernel (any shape and stride, one thread per output),
 //       softmax_rows_kernel (f32 scores -> bf16 probabilities), attention64_kernel (fused
 //       softmax(alpha Q.K^T).V for head dimension 64).
@@ -35,6 +39,7 @@
 #include "nimble_probe.h"
 #include "probe_kernels.h"
 #include "skinny_kernel.h"
+#include "stream_kernel.h"
 
 namespace nimble {
 
@@ -92,11 +97,27 @@ static int launch_ring(const GemmArgs& g, const nimble_plan& p, hipStream_t st) 
   return check_hip(hipGetLastError(), "ring kernel launch");
 }
 
+// Whether the LDS-staged streaming kernel can run a weight-streaming launch: one 16-row tile per
+// workgroup, K in whole 64-wide stages (the LSTM cell: its x | h boundary too), 32-bit lane offsets.
+static bool stream_kernel_ok(bool lstm, int rows_per_block, int64_t N, int64_t K, int64_t Ix) {
+  return rows_per_block <= 16 && stream_kernel_shape_ok(N, K) && (!lstm || (Ix & 63) == 0);
+}
+
 template <bool LSTM>
 static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t st) {
   dim3 grid(p.grid[0], p.grid[1], 1), block(256);
   // 16-row tiles per workgroup: the rows spread evenly over the plan's row blocks (at most 4 each)
   const int mt = (s.M + 16 * (int)p.grid[1] - 1) / (16 * (int)p.grid[1]);
+  if (stream_kernel_ok(LSTM, 16 * mt, s.N, s.K, s.Ix)) {
+    // eight waves with three stages each; up to 8 rows the activation tile is 8 rows (measured on a
+    // 134 MB layer from HBM: 23.9 us at one row, 25.0 at four; the 16-row tile 24.7 and 25.6, and 27.9 at
+    // sixteen rows; four waves per workgroup 27.9-30.5 us whatever the ring depth)
+    if (s.M <= 8)
+      hipLaunchKernelGGL((stream_kernel<LSTM, 3, 8, 8>), grid, dim3(512), 0, st, s);
+    else
+      hipLaunchKernelGGL((stream_kernel<LSTM, 3, 8, 16>), grid, dim3(512), 0, st, s);
+    return check_hip(hipGetLastError(), "stream kernel launch");
+  }
   switch (mt) {
     case 1:
       // a grid that leaves compute units with one workgroup at most, and more than one batch of

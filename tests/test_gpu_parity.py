@@ -243,6 +243,22 @@ def test_skinny_every_M_and_ragged_shapes(rt, nb):
     _sweep(rt, nb, 1, N=768, K=3072, Ms=[1, 2, 3, 4, 8, 16, 31, 64], epilogue="bias_gelu")
 
 
+def test_streaming_kernel_stage_counts_row_blocks_and_ragged_N(rt, nb):
+    """The LDS-staged streaming kernel (weight streaming with K in whole 64-wide stages): every M up
+    to two 16-row blocks and a ragged third, K of 1, 2, 3, 8, 9, 17 and 50 stages (waves with no stage,
+    with fewer stages than ring slots, with unequal shares), N not a multiple of 16, both output types."""
+    for K in (64, 128, 192, 512, 576, 1088, 3200):
+        assert nb.dense_plan(16, 160, K).name == "skinny16"
+        _sweep(rt, nb, 1, N=160, K=K, Ms=[1, 2, 7, 8, 9, 15, 16, 17, 33], epilogue="bias")
+    _sweep(rt, nb, 1, N=200, K=256, Ms=range(1, 50), epilogue="bias_gelu")           # N % 16 = 8
+    _sweep(rt, nb, 1, N=24, K=64, Ms=[1, 8, 9, 16], epilogue="none", out_dtype=1)
+    _sweep(rt, nb, -1, N=8192, K=1024, Ms=[1, 5, 8, 9, 16], epilogue="bias", out_dtype=1)
+    # a layer the dispatch function takes to come from HBM (134 MB): one block of up to 16 rows
+    p = nb.dense_plan(16, 8192, 8192)
+    assert p.name == "skinny16" and p.grid[1] == 1
+    _sweep(rt, nb, -1, N=8192, K=8192, Ms=[1, 8, 16], epilogue="bias")
+
+
 def test_generic_kernel_any_shape(rt, nb):
     _sweep(rt, nb, 0, N=33, K=7, Ms=[1, 2, 17, 40], epilogue="bias_gelu")
     _sweep(rt, nb, 0, N=5, K=100, Ms=[3, 16], epilogue="none", out_dtype=1)
@@ -495,7 +511,7 @@ def test_lstm_one_step_at_every_batch_size(rt, nb):
         _check(cg[:B], rc, ("c pre", B), f32=True)
         _check(hg[:B], rh, ("h pre", B))
         _check(hg[:B], ref_h, ("h pre vs fused oracle", B))
-    assert blocks == {1, 2}, blocks
+    assert blocks == {1, 2, 3, 4}, blocks   # 16-row blocks: the streaming kernel at every B
 
 
 def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
@@ -522,7 +538,9 @@ def test_lstm_closed_forms_and_aliasing_on_gpu(rt, nb):
     h, c = rt.lstm_step(to_dev(x), to_dev(h0), to_dev(zero_w), to_dev(bb), f32_to_dev(c0))
     assert np.max(np.abs(from_dev(c) - c0)) < 1e-6
     # ragged H (not a multiple of 4 units per workgroup is impossible: H % 8 == 0), ragged B
-    for (B2, H2, Ix2) in [(5, 8, 8), (70, 24, 16), (3, 512, 0)]:
+    # (the last four: K and Ix in whole 64-wide stages, i.e. the streaming kernel, one to five row blocks)
+    for (B2, H2, Ix2) in [(5, 8, 8), (70, 24, 16), (3, 512, 0), (7, 64, 128), (20, 192, 64), (16, 136, 120),
+                          (33, 64, 0), (70, 128, 128)]:
         rng2 = np.random.default_rng(B2)
         xx = wl.uniform_bf16(rng2, (B2, Ix2))
         hh = wl.uniform_bf16(rng2, (B2, H2))

@@ -133,16 +133,26 @@ def test_auto_dispatch_table():
         assert p.name in ("skinny16", "t32x128", "t64x128")
         assert p.k * p.bm + p.r == M
         if p.name == "skinny16":
-            # 128 column groups of 16 weight rows: up to two row blocks keep the grid within the
-            # chip's 256 compute units; each block holds at most four 16-row tiles
+            # 128 column groups of 16 weight rows; K is whole 64-wide stages and the layer is small
+            # enough to stay in the caches, so the rows go in blocks of 16 (the streaming kernel)
             blocks = p.grid[1]
-            assert p.grid[0] == 128 and blocks == max(1, min(-(-M // 16), 2))
-            assert -(-M // (16 * blocks)) <= 4
+            assert p.grid[0] == 128 and blocks == -(-M // 16)
+        if M <= 16:
+            assert p.name == "skinny16"
     assert nb.dense_plan(1, 2048, 1024).name == "skinny16"
-    # a narrow layer spreads its rows over more workgroups, a wide one keeps one block per 64 rows
+    # cache-resident layers in whole 64-wide K stages: blocks of 16 rows, whatever the width
     assert nb.dense_plan(64, 768, 768, force_variant=1).grid[:2] == (48, 4)
-    assert nb.dense_plan(64, 4096, 1024, force_variant=1).grid[:2] == (256, 1)
-    assert nb.dense_plan(200, 4096, 1024, force_variant=1).grid[:2] == (256, 4)
+    assert nb.dense_plan(64, 4096, 1024, force_variant=1).grid[:2] == (256, 4)
+    assert nb.dense_plan(200, 4096, 1024, force_variant=1).grid[:2] == (256, 13)
+    # K not in whole stages: the register-layout kernel.  A narrow layer spreads its rows over more
+    # workgroups (each block at most four 16-row tiles), a wide one keeps one block per 64 rows
+    assert nb.dense_plan(64, 768, 776, force_variant=1).grid[:2] == (48, 4)
+    assert nb.dense_plan(64, 4096, 1032, force_variant=1).grid[:2] == (256, 1)
+    assert nb.dense_plan(200, 4096, 1032, force_variant=1).grid[:2] == (256, 4)
+    # a layer streamed from HBM: up to 16 rows the streaming kernel, one block; beyond that one block per
+    # 64 rows so that the weights cross HBM once
+    assert nb.dense_plan(16, 8192, 8192).name == "skinny16" and nb.dense_plan(16, 8192, 8192).grid[:2] == (512, 1)
+    assert nb.dense_plan(64, 8192, 8192, force_variant=1).grid[:2] == (512, 1)
     assert nb.dense_plan(65, 2048, 1024).name.startswith("t")
     assert nb.dense_plan(8192, 4096, 1024).name in ("t256x256", "t256x128")
     assert nb.dense_plan(8192, 4096, 1024).residue_copy == 0
@@ -228,9 +238,14 @@ def test_lstm_plan():
     for B in range(0, 130):
         p = nb.lstm_plan(B, 512, 512)
         assert p.k * 16 + p.r == B and p.grid[0] == 128
-        # row blocks: at most four 16-row tiles each, together covering B; as many as keep the
-        # grid within one workgroup per compute unit (128 column groups -> 2), more only when B forces it
+        # row blocks of 16 (Ix and K in whole 64-wide stages, 4 MB of weights: the streaming kernel)
         blocks = p.grid[1]
+        assert blocks == max(1, -(-B // 16))
+        # x | h boundary not on a stage boundary: the register-layout kernel; row blocks of at most four
+        # 16-row tiles each, as many as keep the grid within one workgroup per compute unit (128 column
+        # groups -> 2), more only when B forces it
+        q = nb.lstm_plan(B, 480, 512)
+        blocks = q.grid[1]
         tiles = -(-B // (16 * blocks))
         assert tiles <= 4 and blocks * 16 * tiles >= B
         assert blocks == max(1, -(-B // 64), min(-(-B // 16), 2))
@@ -316,6 +331,8 @@ def test_plan_invariants_on_random_shapes():
         if p.name == "skinny16":
             blocks = p.grid[1]
             assert p.grid[0] == -(-N // 16) and -(-M // (16 * blocks)) <= 4 and p.workspace_bytes == 0
+            if K % 64 == 0 and N * K * 2 <= 64e6:
+                assert blocks == -(-M // 16)
             continue
         rows = p.split_rows if p.split_rows else M
         assert p.grid[0] == -(-rows // p.bm) * -(-N // p.bn)
