@@ -538,12 +538,56 @@ def two_requests_in_flight(steps: int = 256, warmup: int = 64):
     return {"TFLOPs": round(flops / t / 1e12, 1), "ms_per_step": round(t / steps * 1e3, 4), "steps": steps}
 
 
+def vendor_reference():
+    """Context, not part of the path: the vendor's tuned GEMM library (hipBLASLt behind torch.matmul) on the two
+    FFN shapes at M = 8192, timed the same way as this library's kernels beside it.  It shows what fraction of the
+    nominal MFMA peak a tuned kernel reaches on these shapes on this GPU."""
+    import torch
+
+    import paper_2006_03031_amd as nb
+    from paper_2006_03031_amd import runtime as rt
+
+    out = {}
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=20):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            s.record()
+            for _ in range(reps):
+                fn()
+            e.record()
+            torch.cuda.synchronize()
+            best = min(best, s.elapsed_time(e) * 1e3 / reps)
+        return best
+
+    for name, (M, N, K), epi in (("ffn1_8192x4096x1024", (8192, 4096, 1024), nb.EPI_BIAS_GELU_ERF),
+                                 ("ffn2_8192x1024x4096", (8192, 1024, 4096), nb.EPI_BIAS)):
+        x = torch.empty((M, K), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+        w = torch.empty((N, K), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+        b = torch.zeros((N,), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        flops = 2.0 * M * N * K
+        t_lib = timed(lambda: torch.matmul(x, w.t(), out=y))
+        t_plain = timed(lambda: rt.dense(x, w, b, nb.EPI_BIAS, out=y))
+        t_epi = timed(lambda: rt.dense(x, w, b, epi, out=y))
+        out[name] = {"vendor_matmul_no_epilogue_us": round(t_lib, 1), "vendor_TFLOPs": round(flops / t_lib / 1e6, 1),
+                     "vendor_frac_of_peak": round(flops / t_lib / 1e6 / PEAK_BF16_TFLOPS, 4),
+                     "this_library_bias_us": round(t_plain, 1), "this_library_config_epilogue_us": round(t_epi, 1),
+                     "this_library_TFLOPs": round(flops / t_epi / 1e6, 1)}
+    return out
+
+
 def _extras():
     out = small_m_probe()
     out.update(config_1_and_3_probe())
     out["allocation"] = allocation_probe()
     out["two_requests_in_flight"] = two_requests_in_flight()
     out["achievable"] = achievable_peaks()
+    out["vendor_gemm_reference"] = vendor_reference()
     return out
 
 

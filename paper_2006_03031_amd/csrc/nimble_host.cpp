@@ -179,11 +179,12 @@ static int64_t skinny_row_blocks(int64_t rows, int64_t N, int64_t K, bool stream
 }
 
 // The weight-streaming kernels, launch latency included.
-// Streaming kernel (blocks of 16 rows): whichever is longer of the weight stream and one wave's
-// walk over its K stages, per round of workgroups.  Measured: a 134 MB layer from HBM 24.0 us at
-// 1..8 rows and 27.9 at 16; cache-resident layers 2.5-2.8 us at K = 768..1024, 3.3-4.1 at K =
-// 3072..4096 (0.14-0.20 us per stage of a wave's eight-way share of K); 17..64 rows on the 8 MB
-// layers 4.2-7.2 us.
+// Streaming kernel (blocks of 16 rows): whichever is longer of the weight stream and the waves'
+// walk over their K stages, round of workgroups after round.  Measured: a 134 MB layer from HBM
+// 24.0 us at 1..8 rows and 27.9 at 16; cache-resident layers 2.5-2.8 us at K = 768..1024, 3.3-4.1 at
+// K = 3072..4096 (0.14-0.20 us per stage of a wave's eight-way share of K); 17..64 rows on the 8 MB
+// layers 4.2-7.2 us; 128 rows on 768 -> 768, 3072 -> 768 and 4096 -> 1024: 4.0, 6.4 and 7.5 us, where the
+// best tile with K cut takes 6.9, 10.5 and 11.3.
 // Register-layout kernel (any K): the activations are re-read once per 16 weight rows, which shows
 // from 32 rows on; N / 16 workgroups only, so a short, wide layer leaves most of the chip idle.
 // Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
@@ -191,12 +192,15 @@ static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
   const double bytes = (double)N * (double)K * 2.0;
   const bool cached = bytes <= kCachedWeightBytes;
   if (stream_kernel_shape_ok(N, K) && (rows <= 16 || cached)) {
+    // rounds of one workgroup per compute unit; a round costs 0.45 us plus a wave's walk over its eighth
+    // of the K stages, later rounds 0.25 us more; every 16-row block re-reads the weights, from L2 at
+    // about 13 TB/s when the layer is cache-resident
     const int64_t blocks16 = ceil_div(rows, 16);
     const int64_t rounds = ceil_div(ceil_div(N, 16) * blocks16, kCUs);
-    const double rate = cached ? 22e6 : (rows <= 8 ? 6.2e6 : 5.26e6);  // bytes per microsecond
-    const double stream = bytes * (cached ? 1.0 : (double)blocks16) / rate;
-    const double walk = (double)ceil_div(ceil_div(K, 64), 8) * (rows <= 8 ? 0.14 : 0.20) * (double)rounds +
-                        0.35 * (double)(rounds - 1);
+    const double rate = cached ? 13e6 : (rows <= 8 ? 6.2e6 : 5.26e6);  // bytes per microsecond
+    const double stream = bytes * (double)blocks16 / rate;
+    const double round_us = 0.45 + (double)ceil_div(ceil_div(K, 64), 8) * (rows <= 8 ? 0.14 : 0.20);
+    const double walk = round_us + (double)(rounds - 1) * (round_us + 0.25);
     return kLaunchUs + (stream > walk ? stream : walk);
   }
   const int64_t nblocks = skinny_row_blocks(rows, N, K, false);
@@ -240,7 +244,10 @@ static Launch best_launch(int64_t batch, int64_t rows, int64_t N, int64_t K, int
                           uint64_t max_workspace, bool allow_skinny) {
   Launch best;
   double skinny_us = -1.0;
-  if (allow_skinny && rows <= 64 && batch == 1) {
+  // weight streaming: up to 64 rows, and beyond that in 16-row blocks of the streaming kernel while
+  // the layer is small enough for the blocks' re-reads to come from L2
+  if (allow_skinny && batch == 1 &&
+      (rows <= 64 || (rows <= 512 && stream_kernel_shape_ok(N, K) && (double)N * (double)K * 2.0 <= kCachedWeightBytes))) {
     skinny_us = skinny_cost_us(rows, N, K);
   }
   for (int v = NIMBLE_VAR_T32x128; v <= NIMBLE_VAR_T256x256; ++v) {
@@ -414,11 +421,15 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     p->k = M / v.bm;
     p->r = (int32_t)(M % v.bm);
     p->residue_copy = (p->r != 0 || N % v.bn != 0 || K % v.bk != 0) ? 1 : 0;
-    p->split_k = 4;  // the four waves of a workgroup each take a quarter of K
     p->grid[0] = (uint32_t)ceil_div(N, v.bn);
     p->grid[1] = (uint32_t)skinny_row_blocks(M, N, K, stream_kernel_shape_ok(N, K));  // up to four 16-row tiles per workgroup
     p->grid[2] = 1;
-    p->block = 256;
+    // the waves of a workgroup split K among them: eight in the streaming kernel (16-row blocks,
+    // 64-wide stages), four in the register-layout kernel
+    const bool streaming = stream_kernel_shape_ok(N, K) && ceil_div(M, (int64_t)p->grid[1]) <= 16;
+    p->split_k = streaming ? 8 : 4;
+    p->bk = streaming ? 64 : v.bk;
+    p->block = streaming ? 512 : 256;
     return NIMBLE_OK;
   }
   if (!tiled_variant_ok(variant, M, N, K))
@@ -602,8 +613,8 @@ int nimble_dense_table_set(int64_t N, int64_t K, int epilogue, const nimble_tabl
     if (e.variant < NIMBLE_VAR_SKINNY16 || e.variant >= NIMBLE_VAR_COUNT)
       return fail(NIMBLE_ERR_ARG, "entry %d: variant %d cannot be tabled", i, e.variant);
     if (e.split_k < 0 || e.split_k > 64) return fail(NIMBLE_ERR_ARG, "entry %d: bad split_k", i);
-    if (e.variant == NIMBLE_VAR_SKINNY16 && e.m_hi > 64)
-      return fail(NIMBLE_ERR_ARG, "entry %d: skinny16 serves M <= 64", i);
+    if (e.variant == NIMBLE_VAR_SKINNY16 && e.m_hi > 64 && !stream_kernel_shape_ok(N, K))
+      return fail(NIMBLE_ERR_ARG, "entry %d: skinny16 serves M <= 64 unless K is whole 64-wide stages", i);
     t.push_back(e);
   }
   g_tables[key] = t;
@@ -660,9 +671,15 @@ int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {
   plan->grid[0] = (uint32_t)ceil_div(H, 4);
   // row blocks as for the weight-streaming dense (4H weight rows; measured at H = 512: 2 blocks
   // of 32 rows at B = 64 take 5.6 us against 7.9 us for one block of 64)
-  plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H, Ix + H, stream_kernel_shape_ok(4 * H, Ix + H) && Ix % 64 == 0);
+  const bool stream_ok = stream_kernel_shape_ok(4 * H, Ix + H) && Ix % 64 == 0;
+  plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H, Ix + H, stream_ok);
   plan->grid[2] = 1;
   plan->block = 256;
+  if (stream_ok && ceil_div(B, (int64_t)plan->grid[1]) <= 16) {  // the streaming kernel: eight waves, 64-wide stages
+    plan->split_k = 8;
+    plan->bk = 64;
+    plan->block = 512;
+  }
   return NIMBLE_OK;
 }
 

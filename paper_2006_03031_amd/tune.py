@@ -110,9 +110,10 @@ def tune_dense(N: int, K: int, epilogue: int, m_ref: int = 64, m_grid: Sequence[
         if times[M][cfg] < (1.0 - margin) * auto[M]:
             lo = M if i == 0 else (grid[i - 1] + M) // 2 + 1
             hi = M if i == len(grid) - 1 else (M + grid[i + 1]) // 2
-            if cfg[0] == 1:
+            if cfg[0] == 1 and K % 64 != 0:     # the register-layout streaming kernel serves up to 64 rows
                 hi = min(hi, 64)
-            table.append([lo, hi, cfg[0], cfg[1]])
+            if lo <= hi:
+                table.append([lo, hi, cfg[0], cfg[1]])
     name = lambda c: f"{nb.variant_name(c[0])}/sk{c[1]}"
     return {
         "N": N, "K": K, "epilogue": epilogue, "m_ref": m_ref, "grid": grid,

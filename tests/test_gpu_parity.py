@@ -219,9 +219,11 @@ def test_split_k_forced_and_auto(rt, nb):
             _sweep(rt, nb, forced, N=bn, K=1024, Ms=[1, bm - 1, bm, bm + 3, 2 * bm + 1], epilogue="bias_gelu")
         _sweep(rt, nb, variant | (3 << 8), N=2 * bn, K=32 * 13, Ms=[70, bm + 70], epilogue="bias", out_dtype=1)
     # auto: mid-size M with long K and few tiles is where the dispatch function cuts K
-    for (M, N, K) in [(100, 768, 3072), (300, 768, 3072), (512, 768, 3072)]:
-        assert nb.dense_plan(M, N, K).split_k > 1
-    _sweep(rt, nb, -1, N=768, K=3072, Ms=[65, 100, 129, 300, 511, 512], epilogue="bias")
+    for (M, N, K) in [(600, 768, 3072), (700, 768, 3072), (300, 768, 3104), (300, 1024, 4096)]:
+        p = nb.dense_plan(M, N, K)
+        assert p.variant >= 2 and p.split_k > 1, (M, N, K, p)
+    _sweep(rt, nb, -1, N=768, K=3072, Ms=[65, 100, 129, 300, 511, 512, 600, 700, 1000], epilogue="bias")
+    _sweep(rt, nb, -1, N=768, K=3104, Ms=[65, 100, 300], epilogue="bias")
     # no workspace: the same shapes must still run (the plan falls back to one launch)
     import torch as _t
     empty = _t.empty(0, dtype=_t.uint8, device="cuda")
@@ -308,10 +310,10 @@ def test_two_requests_in_flight_on_two_streams(rt, nb):
     N, K = 768, 3072   # K-split plans at these M
     w, b = wl.normal_bf16(rng, (N, K)), wl.uniform_bf16(rng, (N,))
     wd, bd = to_dev(w), to_dev(b)
-    Ms = [40, 130, 257, 512, 96, 300]
+    Ms = [40, 530, 257, 700, 96, 600]
     xs = [to_dev(wl.uniform_bf16(rng, (M, K))) for M in Ms]
     alone = [bits_from_dev(rt.dense(x, wd, bd, nb.EPI_BIAS)) for x in xs]
-    assert any(nb.dense_plan(M, N, K).split_k > 1 for M in Ms)
+    assert sum(nb.dense_plan(M, N, K).split_k > 1 and nb.dense_plan(M, N, K).variant >= 2 for M in Ms) >= 2
     torch.cuda.synchronize()
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     spaces = [torch.empty(rt.WORKSPACE_BYTES, dtype=torch.uint8, device="cuda") for _ in streams]

@@ -153,7 +153,12 @@ def test_auto_dispatch_table():
     # 64 rows so that the weights cross HBM once
     assert nb.dense_plan(16, 8192, 8192).name == "skinny16" and nb.dense_plan(16, 8192, 8192).grid[:2] == (512, 1)
     assert nb.dense_plan(64, 8192, 8192, force_variant=1).grid[:2] == (512, 1)
-    assert nb.dense_plan(65, 2048, 1024).name.startswith("t")
+    assert nb.dense_plan(65, 2048, 1032).name.startswith("t")     # K not in whole stages: 64 rows at most
+    assert nb.dense_plan(600, 2048, 1024).name.startswith("t")
+    p = nb.dense_plan(16, 2048, 1024)
+    assert (p.block, p.split_k, p.bk) == (512, 8, 64)             # the streaming kernel's launch shape
+    p = nb.dense_plan(16, 2048, 1032)
+    assert (p.block, p.split_k, p.bk) == (256, 4, 32)
     assert nb.dense_plan(8192, 4096, 1024).name in ("t256x256", "t256x128")
     assert nb.dense_plan(8192, 4096, 1024).residue_copy == 0
     # one row past a tile boundary: either the r != 0 copy, or the split dispatch
@@ -390,7 +395,7 @@ def test_batch_matmul_plans_are_one_launch_covering_every_row():
                 if not p.residue_copy:
                     assert M % p.bm == 0 and N % p.bn == 0 and K % p.bk == 0, (T, M, N, K, p)
             if p.name == "skinny16":
-                assert T == 1 and trans_b and M <= 64
+                assert T == 1 and trans_b and M <= 512
 
 
 def test_lstm_pre_shape_matches_oracle():
@@ -450,12 +455,20 @@ def test_tuned_table_overrides_the_cost_model():
         for M, p in before.items():
             assert nb.dense_plan(M, N, K, epi) == p
         # malformed entries are refused and leave no table behind
-        for bad in [[(5, 4, 3, 1)], [(-1, 4, 3, 1)], [(1, 4, 0, 1)], [(1, 4, 7, 1)], [(1, 65, 1, 1)], [(1, 4, 3, 65)]]:
+        for bad in [[(5, 4, 3, 1)], [(-1, 4, 3, 1)], [(1, 4, 0, 1)], [(1, 4, 7, 1)], [(1, 4, 3, 65)]]:
             with pytest.raises(nb.NimbleError) as e:
                 nb.dense_table_set(N, K, epi, bad)
             assert e.value.code == -8
             assert nb.dense_plan(4, N, K, epi).name == "skinny16"
         assert nb.dense_plan(100, N, K, epi) == before[100]
+        # weight streaming beyond 64 rows can be tabled only where the streaming kernel runs (K in whole
+        # 64-wide stages: rows go in blocks of 16)
+        with pytest.raises(nb.NimbleError):
+            nb.dense_table_set(N, K + 8, epi, [(1, 65, 1, 1)])
+        nb.dense_table_set(N, K, epi, [(65, 200, 1, 1)])
+        p = nb.dense_plan(200, N, K, epi)
+        assert p.name == "skinny16" and p.grid[:2] == (48, 13)
+        nb.dense_table_set(N, K, epi, [])
     finally:
         nb.dense_table_set(N, K, epi, [])
         nb.dense_table_set(N, K + 8, epi, [])

@@ -25,7 +25,7 @@ def test_no_alloc_dense_two_calls_in_a_row_match_the_workspace_entry_point():
     stream = torch.cuda.current_stream().cuda_stream
     # the first call cuts K (partial sums in the scratch), the second is smaller and cuts K again on
     # what the first left behind, the third streams the weights and uses no scratch at all
-    cases = [(300, nb.EPI_BIAS_GELU_ERF, "bias_gelu"), (100, nb.EPI_BIAS, "bias"), (8, nb.EPI_BIAS, "bias")]
+    cases = [(700, nb.EPI_BIAS_GELU_ERF, "bias_gelu"), (600, nb.EPI_BIAS, "bias"), (8, nb.EPI_BIAS, "bias")]
     plans = [nb.dense_plan(M, N, K, epi) for M, epi, _ in cases]
     assert plans[0].split_k > 1 and plans[1].split_k > 1 and plans[1].workspace_bytes < plans[0].workspace_bytes
     assert plans[2].workspace_bytes == 0
@@ -59,8 +59,8 @@ def test_no_alloc_dense_two_calls_in_a_row_match_the_workspace_entry_point():
     free_after, _ = torch.cuda.mem_get_info()
     assert free_after == free_before, "device memory was allocated or freed during the calls"
     # f32 output and M = 0
-    y32 = torch.empty((300, N), dtype=torch.float32, device="cuda")
-    nb.nimble_dense_noalloc_dyn(xd[0].data_ptr(), wd.data_ptr(), bd.data_ptr(), y32.data_ptr(), 300, N, K,
+    y32 = torch.empty((700, N), dtype=torch.float32, device="cuda")
+    nb.nimble_dense_noalloc_dyn(xd[0].data_ptr(), wd.data_ptr(), bd.data_ptr(), y32.data_ptr(), 700, N, K,
                                 nb.EPI_BIAS, nb.F32, stream)
     torch.cuda.synchronize()
     assert oracle.normwise_rel_error(from_dev(y32), oracle.dense(xs[0].f32, w.f32, b.f32, "bias")) <= 1e-5
