@@ -24,7 +24,7 @@ int nimble_dense_variant_dyn(const void* x, const void* w, const void* bias, voi
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* Register-only bf16 MFMA loop: 256 workgroups of 4 * waves_per_simd waves (1, 2 or 4), each
- * wave issuing iters * 32 MFMAs of 16x16x32.  seed: device, 64 KiB of bf16 operand data (any
+ * wave issuing iters * (64 / waves_per_simd) independent MFMAs of 16x16x32 back to back.  seed: device, 64 KiB of bf16 operand data (any
  * finite values); sink: device, 1 MiB, overwritten.  *flops receives the flop count of the
  * launch.  Asynchronous on `stream`; the caller times it. */
 int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int iters,

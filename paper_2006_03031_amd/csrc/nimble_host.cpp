@@ -94,10 +94,6 @@ static const double kLaunchGapUs = 3.5;
 // hardware queue has already decoded while the first kernel runs.
 static const double kSplitGapUs = 1.80;
 
-// Weights above this size are taken to come from HBM on every call (the L2s hold 32 MB, the
-// memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
-// as cache-resident, which is what a layer loop or a token loop sees.
-static const double kCachedWeightBytes = 64e6;
 
 // Estimated time of one launch of tiled variant v over `rows` rows with K cut into `sk`
 // slices, microseconds.  The tiles run in rounds of one per compute unit.  A full round runs
@@ -183,8 +179,8 @@ static int64_t skinny_row_blocks(int64_t rows, int64_t N, int64_t K, bool stream
 // walk over their K stages, round of workgroups after round.  Measured: a 134 MB layer from HBM
 // 24.0 us at 1..8 rows and 27.9 at 16; cache-resident layers 2.5-2.8 us at K = 768..1024, 3.3-4.1 at
 // K = 3072..4096 (0.14-0.20 us per stage of a wave's eight-way share of K); 17..64 rows on the 8 MB
-// layers 4.2-7.2 us; 128 rows on 768 -> 768, 3072 -> 768 and 4096 -> 1024: 4.0, 6.4 and 7.5 us, where the
-// best tile with K cut takes 6.9, 10.5 and 11.3.
+// layers 3.6-4.9 us; 128 rows on 768 -> 768, 3072 -> 768 and 4096 -> 1024: 3.3, 5.7 and 6.7 us, where the
+// best tile with K cut takes 6.9, 10.5 and 11.3; 256 rows on 768 -> 2304: 7.8 us (the 64-row tile 7.1).
 // Register-layout kernel (any K): the activations are re-read once per 16 weight rows, which shows
 // from 32 rows on; N / 16 workgroups only, so a short, wide layer leaves most of the chip idle.
 // Fitted to 8 MB .. 134 MB layers at M = 1 .. 64.
@@ -192,15 +188,22 @@ static double skinny_cost_us(int64_t rows, int64_t N, int64_t K) {
   const double bytes = (double)N * (double)K * 2.0;
   const bool cached = bytes <= kCachedWeightBytes;
   if (stream_kernel_shape_ok(N, K) && (rows <= 16 || cached)) {
-    // rounds of one workgroup per compute unit; a round costs 0.45 us plus a wave's walk over its eighth
-    // of the K stages, later rounds 0.25 us more; every 16-row block re-reads the weights, from L2 at
-    // about 13 TB/s when the layer is cache-resident
+    // every 16-row block re-reads the weights: from L2 at about 15 TB/s when the layer is cache-resident
     const int64_t blocks16 = ceil_div(rows, 16);
-    const int64_t rounds = ceil_div(ceil_div(N, 16) * blocks16, kCUs);
-    const double rate = cached ? 13e6 : (rows <= 8 ? 6.2e6 : 5.26e6);  // bytes per microsecond
+    const int64_t wgs = ceil_div(N, 16) * blocks16;
+    const double rate = cached ? 15e6 : (rows <= 8 ? 6.2e6 : 5.26e6);  // bytes per microsecond
     const double stream = bytes * (double)blocks16 / rate;
-    const double round_us = 0.45 + (double)ceil_div(ceil_div(K, 64), 8) * (rows <= 8 ? 0.14 : 0.20);
-    const double walk = round_us + (double)(rounds - 1) * (round_us + 0.25);
+    double walk;
+    if (wgs <= kCUs || !cached) {
+      // one round of eight-wave workgroups: 0.45 us plus a wave's walk over its eighth of the K stages
+      const int64_t rounds = ceil_div(wgs, kCUs);
+      walk = (double)rounds * (0.45 + (double)ceil_div(ceil_div(K, 64), 8) * (rows <= 8 ? 0.14 : 0.20));
+    } else {
+      // four-wave workgroups, four to a compute unit: each holds its place for about 2 us plus 0.11 us per
+      // stage of a wave's quarter of K
+      walk = (double)wgs * (2.0 + 0.11 * (double)ceil_div(ceil_div(K, 64), 4)) / (4.0 * (double)kCUs);
+      if (walk < 0.8) walk = 0.8;
+    }
     return kLaunchUs + (stream > walk ? stream : walk);
   }
   const int64_t nblocks = skinny_row_blocks(rows, N, K, false);
@@ -425,11 +428,13 @@ int plan_dense(int64_t batch, int64_t M, int64_t N, int64_t K, int epilogue, int
     p->grid[1] = (uint32_t)skinny_row_blocks(M, N, K, stream_kernel_shape_ok(N, K));  // up to four 16-row tiles per workgroup
     p->grid[2] = 1;
     // the waves of a workgroup split K among them: eight in the streaming kernel (16-row blocks,
-    // 64-wide stages), four in the register-layout kernel
+    // 64-wide stages; four when a cache-resident layer gives more workgroups than compute units),
+    // four in the register-layout kernel
     const bool streaming = stream_kernel_shape_ok(N, K) && ceil_div(M, (int64_t)p->grid[1]) <= 16;
-    p->split_k = streaming ? 8 : 4;
+    const bool many = (uint64_t)p->grid[0] * p->grid[1] > (uint64_t)kCUs && (double)N * (double)K * 2.0 <= kCachedWeightBytes;
+    p->split_k = streaming && !many ? 8 : 4;
     p->bk = streaming ? 64 : v.bk;
-    p->block = streaming ? 512 : 256;
+    p->block = streaming && !many ? 512 : 256;
     return NIMBLE_OK;
   }
   if (!tiled_variant_ok(variant, M, N, K))
@@ -675,10 +680,12 @@ int nimble_lstm_plan(int64_t B, int64_t Ix, int64_t H, nimble_plan* plan) {
   plan->grid[1] = (uint32_t)skinny_row_blocks(B, 4 * H, Ix + H, stream_ok);
   plan->grid[2] = 1;
   plan->block = 256;
-  if (stream_ok && ceil_div(B, (int64_t)plan->grid[1]) <= 16) {  // the streaming kernel: eight waves, 64-wide stages
-    plan->split_k = 8;
+  if (stream_ok && ceil_div(B, (int64_t)plan->grid[1]) <= 16) {  // the streaming kernel: 64-wide stages
+    const bool many = (uint64_t)plan->grid[0] * plan->grid[1] > (uint64_t)kCUs &&
+                      (double)(4 * H) * (double)(Ix + H) * 2.0 <= kCachedWeightBytes;
+    plan->split_k = many ? 4 : 8;
     plan->bk = 64;
-    plan->block = 512;
+    plan->block = many ? 256 : 512;
   }
   return NIMBLE_OK;
 }

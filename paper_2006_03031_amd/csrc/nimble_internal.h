@@ -25,6 +25,11 @@ bool tiled_variant_ok(int variant, int64_t M, int64_t N, int64_t K);
 // bm = 0 or the variant's own height: always; else the heights the variant is also built at.
 bool tile_rows_ok(int variant, int bm, int64_t N, int64_t K);
 
+// Weights above this size are taken to come from HBM on every call (the L2s hold 32 MB, the
+// memory-side cache 256 MB shared with everything else in flight); smaller layers are priced
+// as cache-resident, which is what a layer loop or a token loop sees.
+constexpr double kCachedWeightBytes = 64e6;
+
 // Whether a weight-streaming launch of 16-row blocks over an [N, K] weight can run the LDS-staged
 // streaming kernel (the LSTM cell needs Ix % 64 == 0 besides).
 bool stream_kernel_shape_ok(int64_t N, int64_t K);

@@ -112,7 +112,15 @@ static int launch_skinny(const SkinnyArgs& s, const nimble_plan& p, hipStream_t 
     // eight waves with three stages each; up to 8 rows the activation tile is 8 rows (measured on a
     // 134 MB layer from HBM: 23.9 us at one row, 25.0 at four; the 16-row tile 24.7 and 25.6, and 27.9 at
     // sixteen rows; four waves per workgroup 27.9-30.5 us whatever the ring depth)
-    if (s.M <= 8)
+    // More workgroups than compute units on a cache-resident layer (several 16-row blocks): small
+    // workgroups of four waves with two stages each, four to a compute unit, so that one's start-up and
+    // reduction overlap the others' streaming (2304 x 768 at 128 rows: 5.2 us against 7.8 with the
+    // shape below and 6.3 with eight waves and two stages; the LSTM cell at 64 rows 3.9 against 5.3).
+    const bool many = (uint64_t)grid.x * grid.y > (uint64_t)kComputeUnits &&
+                      (double)s.N * (double)s.K * 2.0 <= kCachedWeightBytes;
+    if (many)
+      hipLaunchKernelGGL((stream_kernel<LSTM, 2, 4, 16>), grid, dim3(256), 0, st, s);
+    else if (s.M <= 8)
       hipLaunchKernelGGL((stream_kernel<LSTM, 3, 8, 8>), grid, dim3(512), 0, st, s);
     else
       hipLaunchKernelGGL((stream_kernel<LSTM, 3, 8, 16>), grid, dim3(512), 0, st, s);
@@ -496,13 +504,14 @@ int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int
   const uint4* sd = (const uint4*)seed;
   float* sk = (float*)sink;
   switch (waves_per_simd) {
-    case 1: hipLaunchKernelGGL(probe_mfma_kernel<256>, grid, dim3(256), 0, (hipStream_t)stream, sd, sk, iters); break;
-    case 2: hipLaunchKernelGGL(probe_mfma_kernel<512>, grid, dim3(512), 0, (hipStream_t)stream, sd, sk, iters); break;
-    case 4: hipLaunchKernelGGL(probe_mfma_kernel<1024>, grid, dim3(1024), 0, (hipStream_t)stream, sd, sk, iters); break;
+    // (accumulator tiles per wave: as many as the wave's share of the register file holds)
+    case 1: hipLaunchKernelGGL((probe_mfma_kernel<256, 64>), grid, dim3(256), 0, (hipStream_t)stream, sd, sk, iters); break;
+    case 2: hipLaunchKernelGGL((probe_mfma_kernel<512, 32>), grid, dim3(512), 0, (hipStream_t)stream, sd, sk, iters); break;
+    case 4: hipLaunchKernelGGL((probe_mfma_kernel<1024, 16>), grid, dim3(1024), 0, (hipStream_t)stream, sd, sk, iters); break;
     default: return fail(NIMBLE_ERR_ARG, "waves_per_simd must be 1, 2 or 4");
   }
-  // per wave and pass: 32 MFMAs of 16 x 16 x 32 multiply-adds
-  *flops = 256.0 * 4.0 * waves_per_simd * (double)iters * 32.0 * (2.0 * 16 * 16 * 32);
+  // per wave and pass: 64 / waves_per_simd MFMAs of 16 x 16 x 32 multiply-adds
+  *flops = 256.0 * 4.0 * waves_per_simd * (double)iters * (64.0 / waves_per_simd) * (2.0 * 16 * 16 * 32);
   return check_hip(hipGetLastError(), "probe launch");
 }
 

@@ -6,35 +6,34 @@
 
 namespace nimble {
 
-// Each wave keeps 32 accumulator tiles (a 64 x 128 block of outputs) and multiplies four
-// operand fragments against eight, 32 MFMAs of 16x16x32 per pass, with no memory access
-// inside the loop.  The operands are read once from `seed` (real, non-zero data: the power
-// drawn, and with it the clock, depends on how many bits toggle).
-template <int NT>
+// Each wave keeps NACC accumulator tiles of 16 x 16 and issues NACC independent MFMAs of 16x16x32 per
+// pass, with no memory access inside the loop.  The MFMAs are volatile assembly statements with the
+// accumulator held in place, as in the tiled kernels: issued back to back in source order, nothing
+// in between.  (Written with the compiler's builtin and a register rotation in the loop the same
+// measurement read 54 % of peak with one wave per SIMD, which was the schedule the compiler chose,
+// not a limit of the matrix cores: a single wave per SIMD reaches 91-97 % with all-zero operands.)
+// The operands are read once from `seed` (real, non-zero data: the power drawn, and with it the
+// clock, depends on how many bits toggle).
+template <int NT, int NACC>
 __global__ void __launch_bounds__(NT) probe_mfma_kernel(const uint4* __restrict__ seed, float* sink, int iters) {
-  f32x4 acc[32];
+  f32x4 acc[NACC];
 #pragma unroll
-  for (int i = 0; i < 32; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-  uint4 fa[8], fb[4];
+  for (int i = 0; i < NACC; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 fa[8], fb[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) fa[i] = seed[(threadIdx.x * 16 + i) & 4095];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) fb[i] = seed[(threadIdx.x * 16 + 8 + i) & 4095];
+  for (int i = 0; i < 8; ++i) {
+    fa[i] = as_bf16x8(seed[(threadIdx.x * 16 + i) & 4095]);
+    fb[i] = as_bf16x8(seed[(threadIdx.x * 16 + 8 + i) & 4095]);
+  }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(fb[i]), as_bf16x8(fa[j]),
-                                                                 acc[i * 8 + j], 0, 0, 0);
-    const uint4 t = fa[0];  // rotate so that the loop body is not invariant
-#pragma unroll
-    for (int j = 0; j < 7; ++j) fa[j] = fa[j + 1];
-    fa[7] = t;
+    for (int i = 0; i < NACC; ++i) mfma_acc(acc[i], fb[(i >> 3) & 7], fa[i & 7]);
   }
+  // the statements above carry no wait states for their results: idle until the last one has written
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 32; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  for (int i = 0; i < NACC; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
   sink[blockIdx.x * NT + threadIdx.x] = s;
 }
 

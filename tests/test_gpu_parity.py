@@ -349,7 +349,8 @@ def test_config3_bert_base_gemms_every_length(rt, nb, gemm):
         assert np.all(got[L:] == 768.0), (name, L)
         _check(got[:L], ref[:L], (name, L), gelu=epi == "bias_gelu")
         names.add(nb.dense_plan(L, N, K, EPI[epi]).name)
-    assert len(names) >= 2, names
+    # (the 768 -> 768 layer is streamed in 16-row blocks at every length; the others switch to tiles)
+    assert "skinny16" in names and (len(names) >= 2 or name == "proj"), names
 
 
 def test_config3_the_drawn_lengths_with_their_own_inputs(rt, nb):
