@@ -43,18 +43,31 @@ class StorageArena:
         self._base_off = (-base) % self.alignment
         self.capacity = int(capacity_bytes)
         self.offset = 0
+        # tensors already carved at (offset, shape, dtype): a request that repeats (the same run-time
+        # shape at the same place of the same request sequence) gets the same view back instead of
+        # three new Python tensor objects, which is what an allocation from the arena would otherwise cost
+        self._views = {}
 
     def reset(self) -> None:
         self.offset = 0
 
     def alloc(self, shape, dtype: int) -> torch.Tensor:
+        key = (self.offset, tuple(shape), dtype)
+        hit = self._views.get(key)
+        if hit is not None:
+            self.offset = hit[1]
+            return hit[0]
         nbytes = nb.storage_bytes(shape, dtype)
         start = (self.offset + self.alignment - 1) // self.alignment * self.alignment
         if start + nbytes > self.capacity:
             raise MemoryError(f"arena of {self.capacity} bytes cannot hold {nbytes} more at offset {start}")
-        self.offset = start + nbytes
         flat = self.storage[self._base_off + start:self._base_off + start + nbytes]
-        return flat.view(_TORCH_DTYPE[dtype]).view(tuple(shape))
+        t = flat.view(_TORCH_DTYPE[dtype]).view(tuple(shape))
+        if len(self._views) >= 4096:
+            self._views.clear()
+        self._views[key] = (t, start + nbytes)
+        self.offset = start + nbytes
+        return t
 
 
 _WORKSPACE = {}
