@@ -69,28 +69,45 @@ def asm_mfma_findings(asm: str, wait_states: int = 18):
                that names an accumulation register written by such an MFMA fewer than
                `wait_states` issue slots earlier (an MFMA counts 8 slots, s_nop N counts N+1);
       spills:  (kernel, block label, count) of scratch accesses in basic blocks that hold such MFMAs
-               (register spills inside a main loop)."""
+               and sit at the deepest loop level at which the kernel has any (register spills inside
+               a main loop; a spill in a stage the compiler peeled off in front of the loop, once per
+               tile, is not one).  Blocks are told apart by their labels and by the compiler's
+               "%bb.N" comments for blocks reached by falling through; the loop level is the one the
+               compiler prints behind either."""
     import re
     hazards, spills = [], []
     kernel, block, in_stmt = None, None, False
-    block_mfma, block_scratch = 0, 0
+    block_mfma, block_scratch, block_depth = 0, 0, 0
     recent = []  # [age in issue slots, registers written] per statement-MFMA still within reach
+    blocks = []  # of the current kernel: (label, loop level, MFMAs, scratch accesses)
 
     def close_block():
-        if block_mfma and block_scratch:
-            spills.append((kernel, block, block_scratch))
+        if block_mfma:
+            blocks.append((block, block_depth, block_mfma, block_scratch))
+
+    def close_kernel():
+        close_block()
+        if blocks:
+            deepest = max(b[1] for b in blocks)
+            spills.extend((kernel, b[0], b[3]) for b in blocks if b[1] == deepest and b[3])
+        blocks.clear()
 
     for no, line in enumerate(asm.split("\n"), 1):
         t = line.strip()
         m = re.match(r"^(_Z\w+):", line)
         if m:
-            close_block()
-            kernel, block, block_mfma, block_scratch, recent = m.group(1), "entry", 0, 0, []
+            close_kernel()
+            kernel, block, block_mfma, block_scratch, block_depth, recent = m.group(1), "entry", 0, 0, 0, []
             continue
-        m = re.match(r"^(\.LBB\w+):", line)
+        m = re.match(r"^(\.LBB\w+):", line) or re.match(r"^; (%bb\.\d+):", line)
         if m:
             close_block()
             block, block_mfma, block_scratch = m.group(1), 0, 0
+            d = re.search(r"Depth=(\d+)", line)
+            block_depth = int(d.group(1)) if d else 0
+            continue
+        if t.startswith(";") and "Loop Header: Depth=" in t and not block_mfma and not block_scratch:
+            block_depth = int(re.search(r"Depth=(\d+)", t).group(1))  # second comment line of a loop header
             continue
         if t.startswith(";;#ASMSTART"):
             in_stmt = True
@@ -119,7 +136,7 @@ def asm_mfma_findings(asm: str, wait_states: int = 18):
                     hazards.append((kernel, no, t))
                     break
         recent = [[age + 1, regs] for age, regs in recent if age + 1 < 4 * wait_states]
-    close_block()
+    close_kernel()
     return hazards, spills
 
 

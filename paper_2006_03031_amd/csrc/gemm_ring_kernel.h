@@ -38,10 +38,26 @@ namespace nimble {
 //   first fragments are read during the second half's MFMAs.
 enum { RING_PINGPONG = 1, RING_SOLO = 2, RING_WIDE = 3 };
 
-template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE>
-__device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
-                                               uint4* smem) {
+// What one tile of a workgroup's walk hands to the next (PF bodies only).
+//   PF: the epilogue stages its output through a small LDS area of its own behind the ring instead
+//   of through the ring, so the ring is free as soon as the last MFMA has its operands: the body
+//   issues the next tile's bias and first S stages before its own epilogue, and the next body
+//   starts on a ring that filled while the epilogue ran.  Loads and stores complete in the order
+//   a wave issued them, so the next body's waits allow for the epilogue's stores (issued after
+//   those loads) by count and its first S-1 stages run while the stores drain.
+struct RingLink {
+  bool filled = false;  // this tile's bias and first S stages were issued by the previous body
+  int stores = -1;      // stores that body issued after them (-1: not known exactly)
+  bool next = false;    // a tile follows whose first stages this body may issue
+  int next_m0 = 0, next_n0 = 0;
+  int parity = 0;       // bias slot of this tile (the next tile's is the other one)
+};
+
+template <int BM, int BN, int WGM, int WGN, int S, bool MEDGE, int MODE, bool PF = false>
+__device__ __forceinline__ int gemm_ring_body(const GemmArgs& g, const int m0, const int n0,
+                                              uint4* smem, const RingLink lk = RingLink{}) {
   constexpr bool WIDE = MODE == RING_WIDE;
+  static_assert(!PF || WIDE, "only the 64-wide ring hands tiles over");
   static_assert(WIDE ? (S == 2 || S == 3) : (S >= 4 || (MODE == RING_SOLO && S == 3)),
                 "the pipeline keeps S-2 stages in flight");
   constexpr int CH = WIDE ? 8 : 4;      // 16-byte chunks per row and stage
@@ -61,7 +77,10 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   static_assert(BN % PASS == 0 && B_LD >= 1, "tile too narrow for the workgroup");
   static_assert(WM % 16 == 0 && WM >= 16, "a wave owns whole 16-row MFMA tiles");
   static_assert(WN % 64 == 0, "the LDS epilogue stages 64-column blocks");
-  static_assert(NW * WM * WN * 2 <= S * (BMP + BN) * CH * 16, "epilogue staging does not fit in the ring");
+  static_assert(PF || NW * WM * WN * 2 <= S * (BMP + BN) * CH * 16, "epilogue staging does not fit in the ring");
+  // stores of the bf16 epilogue per wave (whole-wave instructions), see RingLink
+  constexpr int NST = (WN / 64) * (WM / 8);
+  static_assert(!PF || NST + (S - 1) * LD + 1 <= 63, "the wait counter holds 63");
   uint4(*As)[BMP * CH] = reinterpret_cast<uint4(*)[BMP * CH]>(smem);
   uint4(*Bs)[BN * CH] = reinterpret_cast<uint4(*)[BN * CH]>(smem + S * BMP * CH);
 
@@ -89,13 +108,16 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   const int ld_row = tid / CH;
   const int ld_c = (tid & (CH - 1)) ^ ((ld_row >> 1) & (CH - 1));
   uint32_t a_off[A_LD];
+  auto set_a_off = [&](const int tile_m0, const bool clamp) {
 #pragma unroll
-  for (int i = 0; i < A_LD; ++i) {
-    int row = ld_row + i * PASS;
-    if (BM % PASS != 0) row = row < BM ? row : BM - 1;
-    if (MEDGE) row = (m0 + row < g.M) ? row : (g.M - 1 - m0);
-    a_off[i] = (uint32_t)(row * g.lda + ld_c * 8) * 2u;
-  }
+    for (int i = 0; i < A_LD; ++i) {
+      int row = ld_row + i * PASS;
+      if (BM % PASS != 0) row = row < BM ? row : BM - 1;
+      if (clamp) row = (tile_m0 + row < g.M) ? row : (g.M - 1 - tile_m0);
+      a_off[i] = (uint32_t)(row * g.lda + ld_c * 8) * 2u;
+    }
+  };
+  set_a_off(m0, MEDGE);
   const uint32_t b_off = (uint32_t)(ld_row * g.ldb + ld_c * 8) * 2u;
   const u16* a_base = A + (long long)m0 * g.lda;
   const u16* b_base = B + (long long)n0 * g.ldb;
@@ -133,20 +155,33 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
   // involved: a load into a register that the compiler cannot see complete may be spilled or
   // copied before its data has arrived.)  The 288- and 320-row tiles leave no LDS for it and load
   // the bias in the epilogue.
-  constexpr bool BIAS_LDS = S * (BMP + BN) * CH * 16 + BN * 2 <= 160 * 1024;
-  u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * CH);
+  constexpr bool BIAS_LDS = PF || S * (BMP + BN) * CH * 16 + BN * 2 <= 160 * 1024;
+  // (PF: two bias slots, used by alternate tiles, then the waves' staging areas)
+  u16* bias_lds = reinterpret_cast<u16*>(smem + S * (BMP + BN) * CH) + (PF ? lk.parity * BN : 0);
   const bool park_bias = BIAS_LDS && g.epilogue != NIMBLE_EPI_NONE && !g.out_f32;
-  if (park_bias && wave < BN / 128) {  // whole waves
-    const int wu = __builtin_amdgcn_readfirstlane(wave);
-    dma4_so((uint32_t)lane * 4u, (const u16*)g.bias + n0 + wu * 128,
-            __builtin_amdgcn_readfirstlane(lds_addr_of(bias_lds)) + wu * 256);
-  }
+  auto fetch_bias = [&](const int tile_n0, u16* dst) {
+    if (park_bias && wave < BN / 128) {  // whole waves
+      const int wu = __builtin_amdgcn_readfirstlane(wave);
+      dma4_so((uint32_t)lane * 4u, (const u16*)g.bias + tile_n0 + wu * 128,
+              __builtin_amdgcn_readfirstlane(lds_addr_of(dst)) + wu * 256);
+    }
+  };
+  // whether the waits of this tile's first S-1 stages may leave the previous epilogue's stores in flight
+  const bool lax = PF && lk.filled && lk.stores == NST;
 
   if constexpr (WIDE) {
+    if (!PF || !lk.filled) {
+      fetch_bias(n0, bias_lds);
 #pragma unroll
-    for (int s = 0; s < S; ++s) dma(s < KS ? s : KS - 1, s);  // always S stages in flight
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * LD) : "memory");  // stage 0 landed
+      for (int s = 0; s < S; ++s) dma(s < KS ? s : KS - 1, s);  // always S stages in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * LD) : "memory");  // stage 0 landed
+    } else if (lax) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NST + (S - 1) * LD) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * LD) : "memory");
+    }
   } else {
+    fetch_bias(n0, bias_lds);
 #pragma unroll
     for (int s = 0; s < S - 1; ++s) {
       if constexpr (MODE == RING_SOLO)
@@ -323,7 +358,10 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       // is here the slot can be refilled, and stage ks+1 has landed when only the S-2 younger
       // stages are in flight
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
+      if (PF && lax && ks < S - 1)  // (uniform) the stores of the previous epilogue are younger than stage ks+1
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NST + (S - 2) * LD) : "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * LD) : "memory");
       __syncthreads();
       // Past the end of K.  S = 2: nothing is loaded (the wait above is for zero loads in flight
       // whether or not a younger stage was issued), which spares the L2->LDS path two stages' worth
@@ -340,6 +378,20 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       half_step(a_rd + slot * (BMP * CH), b_rd + slot * (BN * CH), T1{}, ld_k0, ld_slot, ks + 1 >= KS);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (S = 3: the loads past the end of K)
+  }
+
+  // PF: every wave is past its last fragment read once it is past this barrier; the ring then takes the
+  // next tile's first stages while the epilogue below runs out of registers and the staging areas
+  if constexpr (PF) {
+    __syncthreads();
+    if (lk.next) {
+      set_a_off(lk.next_m0, true);
+      a_base = A + (long long)lk.next_m0 * g.lda;
+      b_base = B + (long long)lk.next_n0 * g.ldb;
+      fetch_bias(lk.next_n0, reinterpret_cast<u16*>(smem + S * (BMP + BN) * CH) + (lk.parity ^ 1) * BN);
+#pragma unroll
+      for (int s = 0; s < S; ++s) dma(s < KS ? s : KS - 1, s);
+    }
   }
 
   // epilogue.  acc[i][j][v] is row m = wm*WM + 16 j + fr_row, column n = wn*WN + 16 i + 4 fr_q + v.
@@ -376,12 +428,44 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
         *(float4*)(C + (long long)m * g.ldc + n) = o;
       }
     }
-    return;
+    return -1;
+  }
+  u16* C = (u16*)g.c + (long long)z * g.sc;
+  constexpr int NH = WN / 64;
+  if constexpr (PF) {
+    // bf16 through the wave's own staging area, 16 rows at a time: [NH][16 rows][128 bytes], chunk c of
+    // row r at slot c ^ ((r >> 1) & 7), written back out as full 128-byte lines.  (Wave-private: no
+    // workgroup barrier; a wave's LDS accesses execute in order.)
+    unsigned char* region = (unsigned char*)(smem + S * (BMP + BN) * CH) + 2 * BN * 2 + wave * (16 * WN * 2);
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i) {
+        const int col = (i & 3) * 16 + fr_q * 4;
+        const int chunk = (col >> 3) ^ ((fr_row >> 1) & 7);
+        uint2 pk;
+        pk.x = pack_bf16x2(epilogue(acc[i][j][0], alpha, bias4[i][0], epi),
+                           epilogue(acc[i][j][1], alpha, bias4[i][1], epi));
+        pk.y = pack_bf16x2(epilogue(acc[i][j][2], alpha, bias4[i][2], epi),
+                           epilogue(acc[i][j][3], alpha, bias4[i][3], epi));
+        *(uint2*)(region + (i >> 2) * (16 * 128) + fr_row * 128 + chunk * 16 + (col & 4) * 2) = pk;
+      }
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          const int row = p * 8 + (lane >> 3);
+          const int c = lane & 7;
+          const uint4 v = *(const uint4*)(region + h * (16 * 128) + row * 128 + ((c ^ ((row >> 1) & 7)) * 16));
+          if (MEDGE && m0 + wm * WM + j * 16 + row >= g.M) continue;
+          *(uint4*)(C + (long long)(m0 + wm * WM + j * 16 + row) * g.ldc + n0 + wn * WN + h * 64 + c * 8) = v;
+        }
+    }
+    return MEDGE ? -1 : NST;
   }
   // bf16: every wave stages its [WM][WN] block in LDS as WN/64 blocks of [WM][64] (rows of 128
   // bytes, chunk c of row r at slot c ^ ((r >> 1) & 7)) and writes it back out as full 128-byte lines
   __syncthreads();  // all fragment reads of the ring are done
-  constexpr int NH = WN / 64;
   unsigned char* region = (unsigned char*)smem + wave * (WM * WN * 2);
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
@@ -399,7 +483,6 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
     }
   }
   // the region is private to the wave: no workgroup barrier, the compiler orders the LDS accesses
-  u16* C = (u16*)g.c + (long long)z * g.sc;
 #pragma unroll
   for (int h = 0; h < NH; ++h)
 #pragma unroll
@@ -411,6 +494,7 @@ __device__ __forceinline__ void gemm_ring_body(const GemmArgs& g, const int m0, 
       uint4* dst = (uint4*)(C + (long long)(m0 + wm * WM + row) * g.ldc + n0 + wn * WN + h * 64 + c * 8);
       *dst = v;
     }
+  return -1;
 }
 
 // S = number of ring stages.  4 keeps two workgroups of the 128x128 tile on a compute unit.  A
@@ -435,7 +519,14 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
   // the ring (which also holds the masked body's two 64-wide tiles), then BN bias values where they fit
   constexpr int kRing = S * (kBmp + BN) * kCh;
   static_assert(kRing >= 2 * (BM + BN) * 8, "the masked body needs two 64-wide tiles");
-  constexpr int kBias = kRing * 16 + BN * 2 <= 160 * 1024 ? BN / 8 : 0;
+  // Wherever two bias slots and a 16-row staging area per wave fit behind a 64-wide ring, a tile's
+  // epilogue leaves the ring alone and the next tile's first stages load while it runs (RingLink).
+  constexpr int kStage = WGM * WGN * 16 * (BN / WGN) * 2 / 16;  // uint4
+  // (never at the price of a workgroup fewer per compute unit)
+  constexpr int kOldBytes = kRing * 16 + (kRing * 16 + BN * 2 <= 160 * 1024 ? BN * 2 : 0);
+  constexpr int kPfBytes = (kRing + 2 * (BN / 8) + kStage) * 16;
+  constexpr bool kPF = WIDE && kPfBytes <= 160 * 1024 && (160 * 1024 / kPfBytes == 160 * 1024 / kOldBytes);
+  constexpr int kBias = kPF ? 2 * (BN / 8) + kStage : (kRing * 16 + BN * 2 <= 160 * 1024 ? BN / 8 : 0);
   __shared__ __attribute__((aligned(16))) uint4 smem[kRing + kBias];
   // A workgroup walks the tiles blockIdx.x, blockIdx.x + gridDim.x, ...: the launcher starts at most
   // as many workgroups as the chip holds at once, so a launch of several rounds pays the 2-3 us it
@@ -443,25 +534,45 @@ __global__ void __launch_bounds__(WGM* WGN * 64) __attribute__((amdgpu_waves_per
   // is a multiple of 8 whenever a workgroup gets more than one tile, so a workgroup's tiles stay in
   // the run of tile ids of its own XCD.)
   const int tiles_total = tiles_m * tiles_n;
+  // launch-wide reasons for the fully masked body: K not whole stages, output rows not 16-byte aligned
+  const bool ragged_launch = RESIDUE && (((g.K & (WIDE ? 63 : 31)) != 0) || ((g.ldc & 7) != 0));
+  RingLink lk;
   for (int t = blockIdx.x; t < tiles_total; t += gridDim.x) {
-    if (t != (int)blockIdx.x) __syncthreads();  // the previous tile's epilogue is done with the LDS
+    // the previous tile's epilogue is done with the LDS (a handed-over ring was free before it began)
+    if (t != (int)blockIdx.x && !lk.filled) __syncthreads();
     int tile_m, tile_n;
     tile_of_block(t, tiles_total, tiles_m, tiles_n, group_m, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
+    if constexpr (kPF) {
+      const int t2 = t + (int)gridDim.x;
+      lk.next = false;
+      if (t2 < tiles_total && !ragged_launch) {
+        int m2, n2;
+        tile_of_block(t2, tiles_total, tiles_m, tiles_n, group_m, m2, n2);
+        lk.next_m0 = m2 * BM;
+        lk.next_n0 = n2 * BN;
+        lk.next = !RESIDUE || lk.next_n0 + BN <= g.N;  // never ahead of a fully masked tile
+      }
+    }
     if (RESIDUE) {
       // the packed epilogue needs 16-byte aligned output rows; K must be whole stages
-      const bool ragged = (n0 + BN > g.N) || ((g.K & (WIDE ? 63 : 31)) != 0) || ((g.ldc & 7) != 0);
+      const bool ragged = ragged_launch || (n0 + BN > g.N);
       if (ragged) {  // ragged N or K, or output rows not 16-byte aligned: the fully masked body
         // (the reduced tile heights are only dispatched to shapes without ragged N or K)
         if constexpr (BM % 128 == 0 || BN == 128) gemm_tile_body<BM, BN, WGM, WGN, true>(g, m0, n0, smem);
+        lk.filled = false;
         continue;
       }
       if (m0 + BM > g.M) {  // the last tile along M: same pipeline, clamped loads, masked stores
-        gemm_ring_body<BM, BN, WGM, WGN, S, true, kMode>(g, m0, n0, smem);
+        lk.stores = gemm_ring_body<BM, BN, WGM, WGN, S, true, kMode, kPF>(g, m0, n0, smem, lk);
+        lk.filled = kPF && lk.next;
+        lk.parity ^= 1;
         continue;
       }
     }
-    gemm_ring_body<BM, BN, WGM, WGN, S, false, kMode>(g, m0, n0, smem);
+    lk.stores = gemm_ring_body<BM, BN, WGM, WGN, S, false, kMode, kPF>(g, m0, n0, smem, lk);
+    lk.filled = kPF && lk.next;
+    lk.parity ^= 1;
   }
 }
 

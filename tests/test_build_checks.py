@@ -56,6 +56,24 @@ def test_checker_reports_scratch_traffic_in_a_block_with_statement_mfmas():
     assert spills == [("_Z4testv", ".LBB0_1", 1)]
 
 
+def test_checker_counts_spills_only_at_the_deepest_loop_level_that_holds_statement_mfmas():
+    mf = STMT_MFMA.format(extra="")
+    # a stage peeled off in front of the K loop (level 1: once per tile) may spill; the K loop (level 2) may not
+    peeled = (".LBB0_1:                                ;   in Loop: Header=BB0_0 Depth=1\n"
+              "\tscratch_load_dword v1, off, off\n" + mf)
+    inner = (".LBB0_2:                                ;   Parent Loop BB0_0 Depth=1\n"
+             "                                        ; =>  This Inner Loop Header: Depth=2\n" + mf +
+             "\ts_cbranch_scc1 .LBB0_2\n")
+    # a block entered by falling through is a block of its own: its spill is not the loop's
+    after = ("; %bb.3:                                ;   in Loop: Header=BB0_0 Depth=1\n"
+             "\tscratch_store_dword off, v1, off\n\ts_endpgm\n")
+    _, spills = build.asm_mfma_findings("_Z4testv:\n" + peeled + inner + after)
+    assert spills == []
+    inner_spilling = inner.replace(mf, "\tscratch_load_dword v2, off, off\n" + mf)
+    _, spills = build.asm_mfma_findings("_Z4testv:\n" + peeled + inner_spilling + after)
+    assert spills == [("_Z4testv", ".LBB0_2", 1)]
+
+
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
 def test_generated_kernels_keep_clear_of_statement_mfma_results_and_do_not_spill_in_main_loops():
     asm = build.device_assembly()

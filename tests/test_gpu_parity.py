@@ -184,6 +184,19 @@ def test_tile_walk_more_tiles_than_resident_workgroups(rt, nb, variant):
     for K in (192, 160):
         _sweep(rt, nb, variant, N=tiles_n * bn, K=K, Ms=[rows], epilogue="bias_gelu", seed=variant)
     _sweep(rt, nb, variant, N=tiles_n * bn - 24, K=64, Ms=[rows - 1], epilogue="bias", seed=variant)
+    # a tile hands the ring to the next one before its own epilogue: without a bias to park (bf16), and
+    # with the f32 epilogue, whose stores the next tile's waits cannot count
+    _sweep(rt, nb, variant, N=tiles_n * bn, K=128, Ms=[rows], epilogue="none", seed=variant)
+    _sweep(rt, nb, variant, N=tiles_n * bn, K=320, Ms=[rows - bm], epilogue="bias", out_dtype=1, seed=variant)
+
+
+def test_tile_walk_at_a_reduced_tile_height(rt, nb):
+    """The 256-wide variant at 160 rows (not a whole number of load passes) over three tiles per
+    workgroup, last tile row ragged."""
+    forced = 6 | (10 << 16)
+    rows = 160 * 200 + 7
+    for K in (64, 192):
+        _sweep(rt, nb, forced, N=4 * 256, K=K, Ms=[rows], epilogue="bias_gelu", seed=K)
 
 
 def test_random_shapes_through_the_dispatch_function(rt, nb):
@@ -818,7 +831,7 @@ def test_batch_matmul_single_batch_large_and_small(rt, nb):
     ref = oracle.batch_matmul(a.f32[:, rows], b.f32, True, 0.5)
     _check(got[rows], ref[0], ("bmm batch 1", M, N, K))
     # few rows: the plan is the weight-streaming kernel, which must scale by alpha
-    for (M, N, K) in [(16, 128, 64), (64, 2304, 768), (5, 64, 128), (33, 512, 256)]:
+    for (M, N, K) in [(16, 128, 64), (64, 2304, 768), (5, 64, 128), (33, 512, 256), (200, 768, 768)]:
         assert nb.batch_matmul_plan(1, M, N, K, True).name == "skinny16", (M, N, K)
         a, b = wl.uniform_bf16(rng, (1, M, K)), wl.uniform_bf16(rng, (1, N, K))
         ref = oracle.batch_matmul(a.f32, b.f32, True, 0.125)
