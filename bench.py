@@ -246,7 +246,7 @@ def small_m_probe():
     del w
     lw = wl.config2_weights()
     dw, db = _to_dev(lw.w), _to_dev(lw.b)
-    for B in (1, 16, 64):
+    for B in (1, 4, 16, 64):
         x = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
         h0 = torch.zeros((B, 512), dtype=torch.bfloat16, device="cuda")
         h1 = torch.zeros_like(h0)
@@ -293,6 +293,37 @@ def small_m_probe():
                                        "roofline": _roof("hbm", nbytes / us_g / 1e3, "GB/s", timing="128-step token loop replayed "
                                                          "as a HIP graph", note="effective: the same 4.2 MB of weights every step "
                                                          "stay in the L2s / memory-side cache")}
+        # the loop over the 128 tokens as ONE launch (recurrent weights in registers, h_t handed over through
+        # memory inside the kernel), timed on the loop alone like the projected-inputs graph minus its dense call
+        if nb.lstm_seq_supported(B, 512):
+            T = 512
+            pre = torch.empty((T, B, 2048), dtype=torch.float32, device="cuda").uniform_(-2, 2)
+            w_h = rt.split_lstm_weight(dw, 512)[1]
+            hz = torch.zeros((B, 512), dtype=torch.bfloat16, device="cuda")
+            cz = torch.zeros((B, 512), dtype=torch.float32, device="cuda")
+            hseq = torch.empty((T, B, 512), dtype=torch.bfloat16, device="cuda")
+            cT = torch.empty((B, 512), dtype=torch.float32, device="cuda")
+            ws = torch.empty(nb.lstm_seq_workspace_bytes(B, 512), dtype=torch.uint8, device="cuda")
+            st = torch.cuda.current_stream().cuda_stream
+
+            def one_launch():
+                nb.nimble_lstm_seq_pre_dyn(pre.data_ptr(), w_h.data_ptr(), hz.data_ptr(), cz.data_ptr(), hseq.data_ptr(),
+                                           cT.data_ptr(), T, B, 512, ws.data_ptr(), ws.numel(), rt.LSTM_SEQ_MAX_POLLS, st)
+            one_launch()
+            gave_up = nb.nimble_lstm_seq_status(ws.data_ptr(), st)
+            best = 1e9
+            for _ in range(3):
+                s.record()
+                one_launch()
+                e.record()
+                torch.cuda.synchronize()
+                best = min(best, s.elapsed_time(e) * 1e3 / T)
+            out[f"lstm_step_B{B}_warm"]["us_per_step_one_launch"] = round(best, 2)
+            out[f"lstm_step_B{B}_warm"]["one_launch_gave_up"] = bool(gave_up)
+            nb_rec = 1024 * 1024 * 2 + 8192 * B + 1024 * B  # recurrent weights + this step's pre + h
+            out[f"lstm_step_B{B}_warm"]["roofline_one_launch"] = _roof(
+                "hbm", nb_rec / best / 1e3, "GB/s", timing="512-token loop in one launch, HIP events",
+                note="effective: the 2.1 MB of recurrent weights stay in registers; a step is bound by the hand-over of h")
         del seq, seq_p
     # the same token loop as bytecode on the interpreter: shape_of, shape function, allocation from
     # the pool and invoke per token (about two dozen coarse instructions), host cost per token split

@@ -265,6 +265,50 @@ int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w
                               const void* c_prev, void* c_out, void* h_out, int64_t B, int64_t H,
                               void* stream);
 
+/* ---- the token loop of a sequence in one launch ----------------------------------------
+ * The evaluation section's LSTM remark (a cell step cannot fill the GPU, so the loop over tokens
+ * is bound by what separates the steps): T steps of nimble_lstm_gates_pre_dyn in a single launch,
+ * the recurrent weights held on chip, h_t handed from step to step through memory.
+ *
+ * Shape function: pre (T,B,4H), h0 (B,H), c0 (B,H), w_h (4H,H) -> h_seq (T,B,H), c_out (B,H);
+ * NIMBLE_ERR_SHAPE when the extents do not fit each other, NIMBLE_ERR_ARG on a negative extent. */
+int nimble_lstm_seq_shape(const int64_t* pre_shape, const int64_t* h0_shape, const int64_t* c0_shape,
+                          const int64_t* wh_shape, int64_t* h_seq_shape, int64_t* c_out_shape);
+
+/* 1 when nimble_lstm_seq_pre_dyn runs (B, H): 1 <= B <= 4, H a multiple of 64, 64 <= H <= 1024
+ * (H/16 workgroups of 64 gate rows, all resident at once); else 0: run the steps one by one. */
+int nimble_lstm_seq_supported(int64_t B, int64_t H);
+
+/* 1 when, besides, the one launch measured faster than one launch per step (H <= 512, or one row up to
+ * H = 1024: a step is then bound by what separates the steps; with more rows or a larger H by the words
+ * every workgroup has to fetch per step); the hint a caller's dispatch takes. */
+int nimble_lstm_seq_preferred(int64_t B, int64_t H);
+
+/* Bytes of device workspace the call needs: 256 bytes of control words, then two (B,H) planes of
+ * 32-bit words.  0 for shapes it does not run. */
+size_t nimble_lstm_seq_workspace_bytes(int64_t B, int64_t H);
+
+/* pre [T,B,4H] f32 (inputs' share of the gates, bias added; gate blocks i, f, g, o), w_h [4H,H] bf16,
+ * h0 [B,H] bf16, c0 [B,H] f32 -> h_seq [T,B,H] bf16 (h_1 .. h_T), c_out [B,H] f32 (c_T; may alias c0).
+ * Device pointers, 16-byte aligned; workspace of nimble_lstm_seq_workspace_bytes(B,H) bytes, owned by the
+ * caller, used by one call at a time.  Two launches are enqueued on `stream` (a fill of the workspace, the
+ * loop); the call does not wait for them.  Results are bit-identical to T calls of
+ * nimble_lstm_gates_pre_dyn.
+ * Every wait inside the kernel is bounded: a wave polls for the other workgroups' h_t at most
+ * `max_polls` times per step (0: none at all, the loop gives up at its first wait), then sets the
+ * give-up word and the whole grid leaves; h_seq and c_out are then unspecified.  The caller reads the word
+ * with nimble_lstm_seq_status after the stream has finished and, if it is set, runs the steps one by one.
+ * Errors: NIMBLE_ERR_SHAPE for (B,H) outside nimble_lstm_seq_supported, NIMBLE_ERR_ARG for T < 0,
+ * NIMBLE_ERR_WORKSPACE, NIMBLE_ERR_NULL, NIMBLE_ERR_ALIGN; nothing is launched then.  T = 0 launches
+ * nothing. */
+int nimble_lstm_seq_pre_dyn(const void* pre, const void* w_h, const void* h0, const void* c0, void* h_seq,
+                            void* c_out, int64_t T, int64_t B, int64_t H, void* workspace,
+                            size_t workspace_bytes, uint32_t max_polls, void* stream);
+
+/* Waits for `stream`, then copies the give-up word of `workspace` to the host:
+ * *gave_up = 0: every step ran; 1: the loop gave up (see above).  NIMBLE_ERR_HIP if the copy fails. */
+int nimble_lstm_seq_status(const void* workspace, void* stream, int* gave_up);
+
 #ifdef __cplusplus
 }
 #endif

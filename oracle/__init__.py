@@ -190,6 +190,18 @@ def lstm_pre_shape(pre_shape, h_shape, c_shape, wh_shape):
     return (B, H), (B, H)
 
 
+def lstm_seq_shape(pre_shape, h0_shape, c0_shape, wh_shape):
+    """Shape function of a whole sequence of such steps (Section 3.2's run-time type check applied to
+    the token loop): pre (T,B,4H), h0 (B,H), c0 (B,H), wh (4H,H) -> every h_t (T,B,H), final c (B,H)."""
+    pre = tuple(int(v) for v in pre_shape)
+    if len(pre) != 3:
+        raise OracleShapeError("lstm_seq_shape: pre must have rank 3")
+    if any(v < 0 for v in pre):
+        raise ValueError("lstm_seq_shape: negative extent")
+    (B, H), _ = lstm_pre_shape(pre[1:], h0_shape, c0_shape, wh_shape)
+    return (pre[0], B, H), (B, H)
+
+
 def lstm_step_pre(pre, h, wh, c) -> Tuple[np.ndarray, np.ndarray]:
     """One LSTM cell step from gates whose input share pre = x.Wx^T + b [B, 4H] was computed
     beforehand (for all tokens in one product); wh [4H, H] are the recurrent columns of the

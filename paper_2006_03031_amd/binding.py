@@ -109,6 +109,14 @@ def load():
     lib.nimble_attention_dyn.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.c_float, vp]
     lib.nimble_lstm_gates_dyn.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
     lib.nimble_lstm_gates_pre_dyn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, vp]
+    lib.nimble_lstm_seq_shape.argtypes = [ip, ip, ip, ip, ip, ip]
+    lib.nimble_lstm_seq_supported.argtypes = [i64, i64]
+    lib.nimble_lstm_seq_preferred.argtypes = [i64, i64]
+    lib.nimble_lstm_seq_workspace_bytes.argtypes = [i64, i64]
+    lib.nimble_lstm_seq_workspace_bytes.restype = ctypes.c_size_t
+    lib.nimble_lstm_seq_pre_dyn.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t,
+                                            ctypes.c_uint32, vp]
+    lib.nimble_lstm_seq_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int)]
     lib.nimble_probe_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.nimble_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     _lib = lib
@@ -201,6 +209,42 @@ def lstm_pre_shape(pre_shape, h_shape, c_shape, wh_shape):
     ws[0], ws[1] = wh_shape
     _check(load().nimble_lstm_pre_shape(ps, hs, cs, ws, ho, co))
     return (ho[0], ho[1]), (co[0], co[1])
+
+
+def lstm_seq_shape(pre_shape, h0_shape, c0_shape, wh_shape):
+    """Shape function of the one-launch token loop: ((T,B,H), (B,H))."""
+    if len(pre_shape) != 3 or any(len(s) != 2 for s in (h0_shape, c0_shape, wh_shape)):
+        raise NimbleError(-2, "lstm sequence expects pre of rank 3 and rank-2 states and weight")
+    ps = (ctypes.c_int64 * 3)(*pre_shape)
+    hs, cs, ws = _arr(h0_shape), _arr(c0_shape), _arr(wh_shape)
+    ho, co = (ctypes.c_int64 * 3)(), (ctypes.c_int64 * 2)()
+    _check(load().nimble_lstm_seq_shape(ps, hs, cs, ws, ho, co))
+    return (ho[0], ho[1], ho[2]), (co[0], co[1])
+
+
+def lstm_seq_supported(B: int, H: int) -> bool:
+    return bool(load().nimble_lstm_seq_supported(B, H))
+
+
+def lstm_seq_preferred(B: int, H: int) -> bool:
+    return bool(load().nimble_lstm_seq_preferred(B, H))
+
+
+def lstm_seq_workspace_bytes(B: int, H: int) -> int:
+    return int(load().nimble_lstm_seq_workspace_bytes(B, H))
+
+
+def nimble_lstm_seq_pre_dyn(pre: int, w_h: int, h0: int, c0: int, h_seq: int, c_out: int, T: int, B: int, H: int,
+                            workspace: int, workspace_bytes: int, max_polls: int, stream: int) -> None:
+    _check(load().nimble_lstm_seq_pre_dyn(pre, w_h, h0, c0, h_seq, c_out, T, B, H, workspace, workspace_bytes,
+                                          max_polls, stream))
+
+
+def nimble_lstm_seq_status(workspace: int, stream: int) -> bool:
+    """Waits for the stream; True when the loop gave up (its outputs are then unspecified)."""
+    flag = ctypes.c_int(0)
+    _check(load().nimble_lstm_seq_status(workspace, stream, ctypes.byref(flag)))
+    return bool(flag.value)
 
 
 def storage_bytes(shape: Sequence[int], dtype: int) -> int:

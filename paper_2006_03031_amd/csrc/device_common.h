@@ -44,7 +44,32 @@ __device__ __forceinline__ float gelu_erf(float v) {
   return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-__device__ __forceinline__ float sigmoidf(float z) { return 1.0f / (1.0f + expf(-z)); }
+// The LSTM cell's nonlinearities on the hardware's exp2 and reciprocal (about 1 ulp each):
+// sigma(z) = 1 / (1 + 2^(-z log2 e)), tanh(z) = 1 - 2 / (1 + 2^(2 z log2 e)); both saturate correctly
+// (2^x -> inf gives 1/inf = 0).  The absolute error is a few 1e-7: far inside the bf16 rounding of h
+// and the f32 bar of c.  The library forms (a division sequence, a branching tanh) are 150-250
+// dependent instructions per cell, which is most of what a one-row step does after its last MFMA.
+__device__ __forceinline__ float sigmoidf(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
+__device__ __forceinline__ float tanh_fast(float z) {
+  return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * z)), 1.0f);
+}
+// One cell update from the four gate pre-activations (i, f, g, o): returns h, writes c.  Every LSTM
+// kernel goes through this one function, with the fused multiply-add spelled out, so that they agree
+// bit for bit.
+// (The one-launch token loop spreads the four gates of a cell over four lanes and then does exactly
+// these operations on the gathered values.)
+__device__ __forceinline__ float lstm_cell(const float (&gate)[4], float c_prev, float& c_new) {
+  const float a_i = sigmoidf(gate[0]), a_f = sigmoidf(gate[1]), a_g = tanh_fast(gate[2]), a_o = sigmoidf(gate[3]);
+  c_new = fmaf(a_f, c_prev, a_i * a_g);
+  return a_o * tanh_fast(c_new);
+}
+// Makes a value opaque to the compiler at this point: what was loaded before a loop stays in its
+// registers instead of being loaded again inside the loop.
+__device__ __forceinline__ void keep_in_registers(uint4& v) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+}
 
 // `bias` is 0 when the epilogue has none, so one fused multiply-add serves every case.
 __device__ __forceinline__ float epilogue(float acc, float alpha, float bias, int epi) {

@@ -561,6 +561,41 @@ int nimble_lstm_pre_shape(const int64_t* pre_shape, const int64_t* h_shape, cons
   return NIMBLE_OK;
 }
 
+int nimble_lstm_seq_shape(const int64_t* pre_shape, const int64_t* h0_shape, const int64_t* c0_shape,
+                          const int64_t* wh_shape, int64_t* h_seq_shape, int64_t* c_out_shape) {
+  clear_error();
+  if (!pre_shape || !h0_shape || !c0_shape || !wh_shape || !h_seq_shape || !c_out_shape)
+    return fail(NIMBLE_ERR_NULL, "null shape pointer");
+  for (int i = 0; i < 3; ++i)
+    if (pre_shape[i] < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  for (int i = 0; i < 2; ++i)
+    if (h0_shape[i] < 0 || c0_shape[i] < 0 || wh_shape[i] < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  const int64_t T = pre_shape[0], B = h0_shape[0], H = h0_shape[1];
+  if (pre_shape[1] != B || c0_shape[0] != B) return fail(NIMBLE_ERR_SHAPE, "lstm sequence: batch extents differ");
+  if (pre_shape[2] != 4 * H) return fail(NIMBLE_ERR_SHAPE, "lstm sequence: pre is not (T,B,4H)");
+  if (c0_shape[1] != H) return fail(NIMBLE_ERR_SHAPE, "lstm sequence: c0 is not (B,H)");
+  if (wh_shape[0] != 4 * H || wh_shape[1] != H) return fail(NIMBLE_ERR_SHAPE, "lstm sequence: w_h is not (4H,H)");
+  h_seq_shape[0] = T;
+  h_seq_shape[1] = c_out_shape[0] = B;
+  h_seq_shape[2] = c_out_shape[1] = H;
+  return NIMBLE_OK;
+}
+
+int nimble_lstm_seq_supported(int64_t B, int64_t H) {
+  return B >= 1 && B <= 4 && H >= 64 && H <= 1024 && (H % 64) == 0;
+}
+
+// Measured against a captured graph of per-step launches (microseconds per step at 1 / 2 / 4 rows):
+// H = 512: 1.89 / 2.02 / 2.41 against 2.65-2.72; H = 1024: 2.71 / 3.20 / 3.98 against 2.85-2.95.
+int nimble_lstm_seq_preferred(int64_t B, int64_t H) {
+  return nimble_lstm_seq_supported(B, H) && (H <= 512 || B == 1);
+}
+
+size_t nimble_lstm_seq_workspace_bytes(int64_t B, int64_t H) {
+  if (!nimble_lstm_seq_supported(B, H)) return 0;
+  return 256 + 2 * (size_t)B * (size_t)H * 4;
+}
+
 int64_t nimble_storage_bytes(const int64_t* shape, int rank, int dtype) {
   clear_error();
   if (rank < 0 || (rank > 0 && !shape)) return fail(NIMBLE_ERR_NULL, "null shape pointer");

@@ -37,6 +37,7 @@
 #include "misc_kernels.h"
 #include "nimble_internal.h"
 #include "nimble_probe.h"
+#include "lstm_seq_kernel.h"
 #include "probe_kernels.h"
 #include "skinny_kernel.h"
 #include "stream_kernel.h"
@@ -492,6 +493,75 @@ int nimble_lstm_gates_pre_dyn(const void* pre, const void* h_prev, const void* w
   s.epilogue = NIMBLE_EPI_BIAS;
   s.alpha = 1.0f;
   return launch_skinny<true>(s, p, (hipStream_t)stream);
+}
+
+int nimble_lstm_seq_pre_dyn(const void* pre, const void* w_h, const void* h0, const void* c0, void* h_seq,
+                            void* c_out, int64_t T, int64_t B, int64_t H, void* workspace,
+                            size_t workspace_bytes, uint32_t max_polls, void* stream) {
+  clear_error();
+  if (T < 0 || B < 0 || H < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
+  if (!nimble_lstm_seq_supported(B, H))
+    return fail(NIMBLE_ERR_SHAPE, "lstm sequence: one launch runs 1 <= B <= 4 and H = 64..1024 in multiples of 64");
+  if (T > (int64_t)1 << 24) return fail(NIMBLE_ERR_ARG, "lstm sequence: more than 2^24 steps");
+  if (T == 0) return NIMBLE_OK;
+  if (!pre || !w_h || !h0 || !c0 || !h_seq || !c_out || !workspace) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
+  if (misaligned(pre) || misaligned(w_h) || misaligned(h0) || misaligned(c0) || misaligned(h_seq) ||
+      misaligned(c_out) || misaligned(workspace))
+    return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
+  if (workspace_bytes < nimble_lstm_seq_workspace_bytes(B, H))
+    return fail(NIMBLE_ERR_WORKSPACE, "lstm sequence: workspace of %zu bytes, %zu needed", workspace_bytes,
+                nimble_lstm_seq_workspace_bytes(B, H));
+  LstmSeqArgs a{};
+  a.pre = (const float*)pre;
+  a.w_h = (const u16*)w_h;
+  a.h0 = (const u16*)h0;
+  a.c0 = (const float*)c0;
+  a.h_seq = (u16*)h_seq;
+  a.c_out = (float*)c_out;
+  a.ctl = (uint32_t*)workspace;
+  a.exch = (uint32_t*)workspace + 64;
+  a.T = (int)T;
+  a.B = (int)B;
+  a.H = (int)H;
+  a.max_polls = max_polls;
+  hipStream_t st = (hipStream_t)stream;
+  const int words = (int)(B * H) > 64 ? (int)(B * H) : 64;
+  hipLaunchKernelGGL(lstm_seq_init_kernel, dim3((words + 255) / 256), dim3(256), 0, st, a);
+  int rc = check_hip(hipGetLastError(), "lstm sequence fill launch");
+  if (rc != NIMBLE_OK) return rc;
+  // H / 16 workgroups (at most 64; 128 with the knob at 2): fewer than the chip holds at once
+  static const int groups = [] {  // measurement knob: groups of 4 units per workgroup
+    const char* e = std::getenv("NIMBLE_LSTM_SEQ_G");
+    const int v = e ? std::atoi(e) : 0;
+    return (v == 2 || v == 4 || v == 8) ? v : 4;
+  }();
+  const bool one_stage = H <= 512;
+  switch (groups) {
+    case 2:
+      if (one_stage) hipLaunchKernelGGL((lstm_seq_kernel<1, 2>), dim3((unsigned)(H / 8)), dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((lstm_seq_kernel<2, 2>), dim3((unsigned)(H / 8)), dim3(512), 0, st, a);
+      break;
+    case 8:
+      if (one_stage) hipLaunchKernelGGL((lstm_seq_kernel<1, 8>), dim3((unsigned)(H / 32)), dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((lstm_seq_kernel<2, 8>), dim3((unsigned)(H / 32)), dim3(512), 0, st, a);
+      break;
+    default:
+      if (one_stage) hipLaunchKernelGGL((lstm_seq_kernel<1, 4>), dim3((unsigned)(H / 16)), dim3(512), 0, st, a);
+      else hipLaunchKernelGGL((lstm_seq_kernel<2, 4>), dim3((unsigned)(H / 16)), dim3(512), 0, st, a);
+      break;
+  }
+  return check_hip(hipGetLastError(), "lstm sequence launch");
+}
+
+int nimble_lstm_seq_status(const void* workspace, void* stream, int* gave_up) {
+  clear_error();
+  if (!workspace || !gave_up) return fail(NIMBLE_ERR_NULL, "null pointer");
+  uint32_t word = 0;
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpy(&word, workspace, sizeof(word), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail(NIMBLE_ERR_HIP, "lstm sequence status: %s", hipGetErrorString(e));
+  *gave_up = word != 0;
+  return NIMBLE_OK;
 }
 
 int nimble_probe_mfma_bf16(const void* seed, void* sink, int waves_per_simd, int iters, double* flops,

@@ -156,9 +156,10 @@ __global__ void __launch_bounds__(256) skinny_kernel(SkinnyArgs s) {
           gate[q] = sum + pre_bias[q];
         }
         const long long o = (long long)m * s.H + unit;
-        const float cn = sigmoidf(gate[1]) * pre_c + sigmoidf(gate[0]) * tanhf(gate[2]);
+        float cn;
+        const float hn = lstm_cell(gate, pre_c, cn);
         s.c_out[o] = cn;
-        ((u16*)s.y)[o] = f2bf(sigmoidf(gate[3]) * tanhf(cn));
+        ((u16*)s.y)[o] = f2bf(hn);
       }
     }
   } else {

@@ -206,6 +206,51 @@ def lstm_step_pre(pre: torch.Tensor, h: torch.Tensor, w_h: torch.Tensor, c: torc
     return h_out, c_out
 
 
+# polls per wait of the one-launch token loop before it gives up (a poll is a round trip to memory, 0.5-1 us:
+# a quarter of a second at the very most)
+LSTM_SEQ_MAX_POLLS = 1 << 18
+
+
+def lstm_sequence_pre(pre: torch.Tensor, w_h: torch.Tensor, h0: torch.Tensor, c0: torch.Tensor,
+                      max_polls: int = LSTM_SEQ_MAX_POLLS, one_launch: Optional[bool] = None,
+                      workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor, bool]:
+    """The token loop of one sequence from the inputs' share of the gates pre [T, B, 4H] (f32):
+    returns (h_seq [T,B,H] bf16, c_T [B,H] f32, ran_in_one_launch).
+
+    one_launch=None: shapes for which nimble_lstm_seq_preferred says so run as one launch
+    (nimble_lstm_seq_pre_dyn); True: every shape nimble_lstm_seq_supported accepts does (others raise);
+    False: none.  After a one-launch run the call waits for the stream and reads the loop's give-up word;
+    if the loop gave up, or one launch was not taken, the steps run one by one through
+    nimble_lstm_gates_pre_dyn, which gives the same bits."""
+    (T, B, H), _ = nb.lstm_seq_shape(tuple(pre.shape), tuple(h0.shape), tuple(c0.shape), tuple(w_h.shape))
+    dev = h0.device
+    h_seq = _alloc((T, B, H), nb.BF16, dev)
+    c_out = _alloc((B, H), nb.F32, dev)
+    pp, wp, hp, cp = _ptr(pre, _F32, "pre"), _ptr(w_h, _BF, "w_h"), _ptr(h0, _BF, "h0"), _ptr(c0, _F32, "c0")
+    if T == 0:
+        c_out.copy_(c0)
+        return h_seq, c_out, False
+    supported = nb.lstm_seq_supported(B, H)
+    if one_launch and not supported:
+        raise nb.NimbleError(-3, f"the one-launch token loop does not run B={B}, H={H}")
+    if one_launch is None:
+        one_launch = nb.lstm_seq_preferred(B, H)
+    if supported and one_launch:
+        need = nb.lstm_seq_workspace_bytes(B, H)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        nb.nimble_lstm_seq_pre_dyn(pp, wp, hp, cp, h_seq.data_ptr(), c_out.data_ptr(), T, B, H,
+                                   _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), max_polls, _stream())
+        if not nb.nimble_lstm_seq_status(workspace.data_ptr(), _stream()):
+            return h_seq, c_out, True
+    st = _stream()
+    c_out.copy_(c0)
+    for t in range(T):
+        nb.nimble_lstm_gates_pre_dyn(pre[t].data_ptr(), (h0 if t == 0 else h_seq[t - 1]).data_ptr(), wp,
+                                     c_out.data_ptr(), c_out.data_ptr(), h_seq[t].data_ptr(), B, H, st)
+    return h_seq, c_out, False
+
+
 def split_lstm_weight(w: torch.Tensor, Ix: int) -> Tuple[torch.Tensor, torch.Tensor]:
     """One-time split of the fused weight [4H, Ix+H] into contiguous input and recurrent halves."""
     return w[:, :Ix].contiguous(), w[:, Ix:].contiguous()

@@ -420,6 +420,45 @@ def test_lstm_pre_shape_matches_oracle():
     assert lib.nimble_lstm_pre_shape(None, four[1], four[2], four[3], out, out) == -1
 
 
+def test_lstm_seq_shape_support_and_refusals():
+    """The one-launch token loop: shape function against the oracle twin, the shapes it runs, its
+    workspace size, and every refusal that is decided before anything is launched."""
+    for T, B, H in [(0, 1, 512), (128, 1, 512), (5, 16, 1024), (3, 40, 72)]:
+        args = ((T, B, 4 * H), (B, H), (B, H), (4 * H, H))
+        assert nb.lstm_seq_shape(*args) == oracle.lstm_seq_shape(*args) == ((T, B, H), (B, H))
+    for bad in [((7, 4, 32), (3, 8), (3, 8), (32, 8)), ((7, 3, 31), (3, 8), (3, 8), (32, 8)),
+                ((7, 3, 32), (3, 8), (3, 9), (32, 8)), ((7, 3, 32), (3, 8), (3, 8), (32, 9))]:
+        with pytest.raises(nb.NimbleError) as e:
+            nb.lstm_seq_shape(*bad)
+        assert e.value.code == -3
+        with pytest.raises(oracle.OracleShapeError):
+            oracle.lstm_seq_shape(*bad)
+    with pytest.raises(nb.NimbleError) as e:
+        nb.lstm_seq_shape((-7, 3, 32), (3, 8), (3, 8), (32, 8))
+    assert e.value.code == -8
+    ok = [(1, 64), (1, 512), (4, 512), (4, 1024), (3, 576)]
+    no = [(0, 512), (5, 512), (16, 512), (1, 32), (1, 96), (1, 1088), (1, 2048), (-1, 512)]
+    assert all(nb.lstm_seq_supported(B, H) for B, H in ok) and not any(nb.lstm_seq_supported(B, H) for B, H in no)
+    assert [nb.lstm_seq_preferred(B, H) for B, H in [(1, 512), (4, 256), (1, 1024), (2, 1024), (5, 512)]] == \
+        [True, True, True, False, False]
+    assert nb.lstm_seq_workspace_bytes(4, 512) == 256 + 2 * 4 * 512 * 4
+    assert nb.lstm_seq_workspace_bytes(5, 512) == 0
+    # refusals: nothing is launched (no GPU here), the message names the reason
+    call = nb.nimble_lstm_seq_pre_dyn
+    a = 4096   # any non-null, 16-byte aligned number: never dereferenced on these paths
+    for args, code in [((a, a, a, a, a, a, 5, 5, 512, a, 1 << 20, 10, 0), -3),
+                       ((a, a, a, a, a, a, 5, 1, 96, a, 1 << 20, 10, 0), -3),
+                       ((a, a, a, a, a, a, -1, 1, 512, a, 1 << 20, 10, 0), -8),
+                       ((a, a, 0, a, a, a, 5, 1, 512, a, 1 << 20, 10, 0), -1),
+                       ((a, a, a, a, a, a, 5, 1, 512, 0, 1 << 20, 10, 0), -1),
+                       ((a, a + 8, a, a, a, a, 5, 1, 512, a, 1 << 20, 10, 0), -5),
+                       ((a, a, a, a, a, a, 5, 1, 512, a, 256 + 2 * 512 * 4 - 1, 10, 0), -6)]:
+        with pytest.raises(nb.NimbleError) as e:
+            call(*args)
+        assert e.value.code == code, (args, e.value)
+    call(a, a, a, a, a, a, 0, 1, 512, a, 1 << 20, 10, 0)   # T = 0: nothing to do, nothing launched
+
+
 def test_tuned_table_overrides_the_cost_model():
     """Section 3.5, tuning: an installed entry decides the dispatch inside its M range and nowhere
     else; entries that cannot run are skipped; count = 0 removes the table."""

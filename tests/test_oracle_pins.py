@@ -604,3 +604,16 @@ def test_lstm_pre_shape_function():
                     oracle.lstm_pre_shape(bad_pre, (B, H), (B, H), (4 * H, H))
     with pytest.raises(oracle.OracleShapeError):
         oracle.lstm_pre_shape((3, 32, 1), (3, 8), (3, 8), (32, 8))
+
+
+def test_lstm_seq_shape_function():
+    """Known answers: T is taken from pre, B and H from h0, every other extent must agree."""
+    assert oracle.lstm_seq_shape((7, 3, 32), (3, 8), (3, 8), (32, 8)) == ((7, 3, 8), (3, 8))
+    assert oracle.lstm_seq_shape((0, 1, 2048), (1, 512), (1, 512), (2048, 512)) == ((0, 1, 512), (1, 512))
+    for bad in [((7, 4, 32), (3, 8), (3, 8), (32, 8)), ((7, 3, 31), (3, 8), (3, 8), (32, 8)),
+                ((7, 3, 32), (3, 8), (3, 9), (32, 8)), ((7, 3, 32), (3, 8), (3, 8), (32, 9)),
+                ((7, 3, 32), (3, 8), (3, 8), (8, 32)), ((3, 32), (3, 8), (3, 8), (32, 8))]:
+        with pytest.raises(oracle.OracleShapeError):
+            oracle.lstm_seq_shape(*bad)
+    with pytest.raises(ValueError):
+        oracle.lstm_seq_shape((-1, 3, 32), (3, 8), (3, 8), (32, 8))
