@@ -251,6 +251,16 @@ def lstm_sequence_pre(pre: torch.Tensor, w_h: torch.Tensor, h0: torch.Tensor, c0
     return h_seq, c_out, False
 
 
+def lstm_sequence(xs: torch.Tensor, w_x: torch.Tensor, w_h: torch.Tensor, bias: torch.Tensor, h0: torch.Tensor,
+                  c0: torch.Tensor, **kw) -> Tuple[torch.Tensor, torch.Tensor, bool]:
+    """A whole sequence xs [T, B, Ix] through the cell: the inputs' share of the gates for all T*B tokens in one
+    dense call (M = T*B dynamic, f32 output), then the token loop (lstm_sequence_pre).  w_x [4H, Ix] and
+    w_h [4H, H] are the two halves of the fused weight (split_lstm_weight)."""
+    T, B, Ix = xs.shape
+    pre = dense(xs.view(T * B, Ix), w_x, bias, nb.EPI_BIAS, nb.F32)
+    return lstm_sequence_pre(pre.view(T, B, w_x.shape[0]), w_h, h0, c0, **kw)
+
+
 def split_lstm_weight(w: torch.Tensor, Ix: int) -> Tuple[torch.Tensor, torch.Tensor]:
     """One-time split of the fused weight [4H, Ix+H] into contiguous input and recurrent halves."""
     return w[:, :Ix].contiguous(), w[:, Ix:].contiguous()

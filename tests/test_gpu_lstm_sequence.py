@@ -140,3 +140,23 @@ def test_unsupported_shapes_run_step_by_step_or_raise(rt, nb):
         pre, w_h, h0, c0 = _case(31, 4, B, H)
         _, _, one = rt.lstm_sequence_pre(f32_to_dev(pre), to_dev(w_h), to_dev(h0), f32_to_dev(c0))
         assert one == nb.lstm_seq_preferred(B, H)
+
+
+def test_whole_sequence_with_projected_inputs_equals_the_captured_graph(rt, nb):
+    """config 2's cell (2048 x 1024): the inputs' product for all tokens in one dense call, then the loop in one
+    launch; the same bits as the captured graph of per-step launches, which test_gpu_parity holds to the oracle."""
+    from gpu_util import to_dev
+    lw = wl.config2_weights()
+    dw, db = to_dev(lw.w), to_dev(lw.b)
+    H, Ix, T = wl.LSTM_H, wl.LSTM_IX, 24
+    w_x, w_h = rt.split_lstm_weight(dw, Ix)
+    for B in (1, 3):
+        xs = to_dev(wl.config2_inputs(50 + B, B, T))
+        h0 = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda")
+        c0 = torch.zeros((B, H), dtype=torch.float32, device="cuda")
+        print(f"sequence B={B}", flush=True)
+        h_seq, c_T, one = rt.lstm_sequence(xs, w_x, w_h, db, h0, c0)
+        assert one == nb.lstm_seq_preferred(B, H) and one
+        graph = rt.LstmSequenceGraph(dw, db, B, T, Ix, H, project_inputs=True)
+        hs, c = graph.run(xs)
+        assert torch.equal(hs, h_seq) and torch.equal(c, c_T)
