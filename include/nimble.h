@@ -236,7 +236,7 @@ int nimble_softmax_rows_dyn(const void* s_f32, void* p_bf16, int64_t rows, int64
  * functions, Section 3.2; both dynamic extents are the same symbol L, Section 3.1):
  *   o[t,i,:] = sum_j softmax_j(alpha * q[t,i,:].k[t,j,:]) * v[t,j,:]
  * q, k, v, o are [heads, L, D] bf16; scores and the softmax in f32, P rounded to bf16 before
- * P.v, f32 accumulation.  Built for D = 64 (NIMBLE_ERR_ARG otherwise: use the three calls). */
+ * P.v, f32 accumulation.  Built for D = 64 and alpha > 0 (NIMBLE_ERR_ARG otherwise: use the three calls). */
 int nimble_attention_dyn(const void* q, const void* k, const void* v, void* o, int64_t heads,
                          int64_t L, int64_t D, float alpha, void* stream);
 

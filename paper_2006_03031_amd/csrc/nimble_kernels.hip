@@ -421,14 +421,19 @@ int nimble_attention_dyn(const void* q, const void* k, const void* v, void* o, i
   clear_error();
   if (heads < 0 || L < 0 || D < 0) return fail(NIMBLE_ERR_ARG, "negative extent");
   if (D != 64) return fail(NIMBLE_ERR_ARG, "fused attention is built for head dimension 64, got %lld", (long long)D);
+  if (!(alpha > 0.0f)) return fail(NIMBLE_ERR_ARG, "fused attention needs a positive score scale, got %g", (double)alpha);
   if (heads > 65535 || L > (1ll << 24)) return fail(NIMBLE_ERR_ARG, "extent too large");
   if (heads == 0 || L == 0) return NIMBLE_OK;
   if (!q || !k || !v || !o) return fail(NIMBLE_ERR_NULL, "null tensor pointer");
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o))
     return fail(NIMBLE_ERR_ALIGN, "device pointers must be 16-byte aligned");
-  dim3 grid((unsigned)((L + 63) / 64), (unsigned)heads), block(256);
-  hipLaunchKernelGGL(attention64_kernel, grid, block, 0, (hipStream_t)stream, (const u16*)q, (const u16*)k,
-                     (const u16*)v, (u16*)o, (int)L, alpha);
+  dim3 grid((unsigned)((L + 63) / 64), (unsigned)heads);
+  static const bool blocks64 = std::getenv("NIMBLE_ATT_BLOCK64") != nullptr;  // measurement knob
+  const u16 *qp = (const u16*)q, *kp = (const u16*)k, *vp = (const u16*)v;
+  if (L <= 64 || blocks64)
+    hipLaunchKernelGGL(attention64_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream, qp, kp, vp, (u16*)o, (int)L, alpha);
+  else
+    hipLaunchKernelGGL(attention64_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream, qp, kp, vp, (u16*)o, (int)L, alpha);
   return check_hip(hipGetLastError(), "attention kernel launch");
 }
 

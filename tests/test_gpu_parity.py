@@ -726,6 +726,17 @@ def test_fused_attention_matches_the_oracle_chain(rt, nb):
         if L % 16 in (0, 1, 15):   # and it agrees with the three-call chain on the GPU to rounding
             _, _, o3 = rt.attention(to_dev(q), to_dev(k), to_dev(v))
             assert _err(from_dev(o), from_dev(o3)) <= TOL, ("O vs chain", L)
+    # other positive scales: sharp rows (the running maximum moves from block to block, single keys dominate)
+    # and nearly flat ones
+    for alpha, L in [(1.0, 200), (0.5, 129), (1e-3, 300), (2.0, 64)]:
+        q, k, v = wl.config4_qkv(200 + L, L)
+        o = rt.fused_attention(to_dev(q), to_dev(k), to_dev(v), alpha=alpha)
+        _, _, ro = oracle.attention(q.f32, k.f32, v.f32, alpha=alpha)
+        _check(from_dev(o), ro, ("O", L, alpha), floor=P_ROUNDED_FLOOR)
+    for bad in (0.0, -0.125):       # the fused softmax works on raw scores: the scale must be positive
+        with pytest.raises(nb.NimbleError) as e:
+            rt.fused_attention(to_dev(q), to_dev(k), to_dev(v), alpha=bad)
+        assert e.value.code == -8
     # closed forms: L = 1 returns V; Q = 0 returns the column mean of V
     q, k, v = wl.config4_qkv(7, 1)
     assert np.array_equal(from_dev(rt.fused_attention(to_dev(q), to_dev(k), to_dev(v))), v.f32)

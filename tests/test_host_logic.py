@@ -277,6 +277,8 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     assert lib.nimble_attention_dyn(None, None, None, None, 12, 5, 64, 0.125, None) == -1
     assert lib.nimble_attention_dyn(16, 32, 48, 72, 12, 5, 64, 0.125, None) == -5
     assert lib.nimble_attention_dyn(16, 32, 48, 64, 12, 5, 80, 0.125, None) == -8
+    for bad_alpha in (0.0, -0.125, float("nan")):   # the fused softmax works on raw scores: the scale must be > 0
+        assert lib.nimble_attention_dyn(16, 32, 48, 64, 12, 5, 64, bad_alpha, None) == -8
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 0, 512, 512, None, 0, None) == 0
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 32, 3, 512, 512, None, 0, None) == -8  # h_out aliases h_prev
     assert lib.nimble_lstm_gates_dyn(16, 32, 48, 64, 80, 96, 112, 3, 511, 512, None, 0, None) == -8
