@@ -634,6 +634,38 @@ def vendor_reference():
                      "vendor_frac_of_peak": round(flops / t_lib / 1e6 / PEAK_BF16_TFLOPS, 4),
                      "this_library_bias_us": round(t_plain, 1), "this_library_config_epilogue_us": round(t_epi, 1),
                      "this_library_TFLOPs": round(flops / t_epi / 1e6, 1)}
+
+    # the BERT-base layers of config 3 at a few lengths, both sides as 20 launches replayed as one HIP graph
+    # (microseconds per call: this library with the layer's epilogue / the vendor's matmul without one)
+    def graph_us(fn, n=20):
+        fn()
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for _ in range(n):
+                fn()
+        gr.replay()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            s.record()
+            gr.replay()
+            e.record()
+            torch.cuda.synchronize()
+            best = min(best, s.elapsed_time(e) * 1e3 / n)
+        return best
+
+    mid = {}
+    for (N, K, epi) in ((2304, 768, nb.EPI_BIAS), (768, 768, nb.EPI_BIAS), (3072, 768, nb.EPI_BIAS_GELU_ERF),
+                        (768, 3072, nb.EPI_BIAS)):
+        w = torch.empty((N, K), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+        b = torch.zeros((N,), dtype=torch.bfloat16, device="cuda")
+        for M in (64, 128, 512, 2048):
+            x = torch.empty((M, K), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            mid[f"{M}x{N}x{K}"] = [round(graph_us(lambda: rt.dense(x, w, b, epi, out=y)), 2),
+                                   round(graph_us(lambda: torch.matmul(x, w.t(), out=y)), 2)]
+    out["bert_base_layers_us_this_library_vs_vendor"] = mid
     return out
 
 
