@@ -160,3 +160,31 @@ def test_whole_sequence_with_projected_inputs_equals_the_captured_graph(rt, nb):
         graph = rt.LstmSequenceGraph(dw, db, B, T, Ix, H, project_inputs=True)
         hs, c = graph.run(xs)
         assert torch.equal(hs, h_seq) and torch.equal(c, c_T)
+
+
+def test_step_tags_wrap_after_65535_steps(rt, nb):
+    """The hand-over words carry a 16-bit step tag with period 65535: a sequence longer than that must still give
+    the bits of the step-by-step path (checked on the last steps and the final cell state) and match the oracle
+    on its last step."""
+    from gpu_util import bits_from_dev, f32_to_dev, from_dev, to_dev
+    T, B, H = 65535 + 700, 1, 64
+    rng = np.random.default_rng([2, 99])
+    pre = rng.uniform(-2.0, 2.0, (T, B, 4 * H)).astype(np.float32)
+    w_h = wl.normal_bf16(rng, (4 * H, H), std=1.0 / np.sqrt(H))
+    h0 = wl.uniform_bf16(rng, (B, H))
+    c0 = rng.uniform(-1.0, 1.0, (B, H)).astype(np.float32)
+    dpre, dw, dh0, dc0 = f32_to_dev(pre), to_dev(w_h), to_dev(h0), f32_to_dev(c0)
+    print(f"one launch T={T}", flush=True)
+    h_seq, c_T, one = rt.lstm_sequence_pre(dpre, dw, dh0, dc0, one_launch=True)
+    assert one
+    print("step by step", flush=True)
+    h2, c2, one2 = rt.lstm_sequence_pre(dpre, dw, dh0, dc0, one_launch=False)
+    assert not one2
+    assert torch.equal(h_seq, h2) and torch.equal(c_T, c2)
+    # the last step from the GPU's state before it (its c through one more step-by-step run of T-1 steps is c2's
+    # predecessor; cheaper: redo the last step with the per-step call from the states of the T-1 prefix)
+    h_prev = h_seq[T - 2]
+    _, c_prev, _ = rt.lstm_sequence_pre(dpre[:T - 1], dw, dh0, dc0, one_launch=True)
+    ref_h, ref_c = oracle.lstm_step_pre(pre[T - 1], from_dev(h_prev), w_h.f32, from_dev(c_prev))
+    _check(from_dev(h_seq[T - 1]), ref_h, ("h", T))
+    _check(from_dev(c_T), ref_c, ("c", T), f32=True)
