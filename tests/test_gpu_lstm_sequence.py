@@ -188,3 +188,30 @@ def test_step_tags_wrap_after_65535_steps(rt, nb):
     ref_h, ref_c = oracle.lstm_step_pre(pre[T - 1], from_dev(h_prev), w_h.f32, from_dev(c_prev))
     _check(from_dev(h_seq[T - 1]), ref_h, ("h", T))
     _check(from_dev(c_T), ref_c, ("c", T), f32=True)
+
+
+def test_the_loop_beside_a_busy_stream_is_right_whether_or_not_it_gives_up(rt, nb):
+    """Large GEMMs keep every compute unit busy on a second stream while the loop is launched: its workgroups
+    may start late or apart, the bounded waits may run out; either way the call returns the step-by-step bits."""
+    from gpu_util import f32_to_dev, to_dev
+    T, B, H = 64, 2, 512
+    pre, w_h, h0, c0 = _case(40, T, B, H)
+    dpre, dw, dh0, dc0 = f32_to_dev(pre), to_dev(w_h), to_dev(h0), f32_to_dev(c0)
+    want_h, want_c, _ = rt.lstm_sequence_pre(dpre, dw, dh0, dc0, one_launch=False)
+    x = torch.empty((8192, 1024), dtype=torch.bfloat16, device="cuda").uniform_(-1, 1)
+    w = torch.empty((4096, 1024), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    b = torch.zeros((4096,), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((8192, 4096), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outcomes = []
+    for rep in range(3):
+        with torch.cuda.stream(side):
+            for _ in range(40):
+                rt.dense(x, w, b, nb.EPI_BIAS, out=y)
+        print(f"loop beside a busy stream, repetition {rep}", flush=True)
+        h, c, one = rt.lstm_sequence_pre(dpre, dw, dh0, dc0, max_polls=1 << 14, one_launch=True)
+        outcomes.append(one)
+        assert torch.equal(h, want_h) and torch.equal(c, want_c), (rep, one)
+        torch.cuda.synchronize()
+    print("ran in one launch:", outcomes)
